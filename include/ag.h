@@ -1,0 +1,200 @@
+/*
+ * ag.h - C ABI of the paged-KV attention library for MI355X (gfx950).
+ *
+ * The library implements the GPU work behind the three request classes of an
+ * agent-serving engine (paper Sec. I, Sec. II-A, Fig. 1):
+ *   cold prefill   - causal attention over a whole prompt that also builds the
+ *                    session's KV cache;
+ *   resume prefill - an appended chunk (a tool's output) attends to the cached
+ *                    prefix and causally to itself;
+ *   short decode   - one query per session over its cached keys and values;
+ * plus the KV append that builds the cache, and CU-masked streams, the AMD
+ * counterpart of the paper's pre-created SM partitions (Sec. III-C), on which
+ * prefill and decode kernels run side by side.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a comment says "host".
+ *     The caller owns every buffer; the library allocates no device memory
+ *     and keeps no state between calls (stream handles excepted).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work and return; they never synchronise.
+ *   - Return value is an ag_status.  Conditions the host can see (null
+ *     pointers, unsupported shapes, bounds that contradict each other, a
+ *     workspace that is too small) are reported BEFORE anything is enqueued.
+ *     Device-resident data (page ids, lengths) is not validated: a page id
+ *     outside [0, num_pages) or a length beyond the host-side bound is
+ *     undefined behaviour, as for any paged-attention kernel.
+ *     ag_last_error() returns a thread-local message for the last failure.
+ *   - Layouts (row-major, innermost last):
+ *       Q, O          [T][Hq][D]        token-major, sessions concatenated
+ *       K_new, V_new  [T][Hkv][D]
+ *       K pool        [num_pages][Hkv][page_size][D]
+ *       V pool        [num_pages][Hkv][D][page_size]   (value pages are stored
+ *                     transposed: the value product contracts over tokens and
+ *                     the matrix cores want the contracted index contiguous)
+ *       block_tables  int32 [B][max_pages_per_seq]; logical page p of session
+ *                     s lives in physical page block_tables[s][p]
+ *       cu_new        int32 [B+1], cu_new[0] = 0, cu_new[s+1]-cu_new[s] = new_lens[s]
+ *   - Logical position j of a session is page j / page_size, slot j % page_size.
+ *   - GQA: query head h reads KV head h / (Hq / Hkv).
+ *   - Ordering (paper Sec. III-C, memory management: a decode must never see
+ *     partly written KV): attention reads keys and values ONLY from the
+ *     pools, so the ag_kv_append that writes a token must precede, on the
+ *     same stream or through an event, any attention call that covers it.
+ *   - Supported: dtype AG_F32 or AG_BF16; head_dim a multiple of 8, <= 256;
+ *     page_size a power of two in [1, 256].  bf16 with head_dim 128 and page_size 16
+ *     runs on the matrix-core kernels; every other supported combination
+ *     runs on the general fp32-arithmetic kernels.
+ */
+#ifndef AG_H
+#define AG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AG_API __attribute__((visibility("default")))
+
+typedef enum {
+    AG_OK = 0,
+    AG_ERR_INVALID_ARG = -1,   /* null pointer, negative size, contradictory bounds */
+    AG_ERR_UNSUPPORTED = -2,   /* dtype / head_dim / page_size outside the supported set */
+    AG_ERR_WORKSPACE = -3,     /* decode workspace smaller than ag_attn_decode_workspace_bytes() */
+    AG_ERR_HIP = -4            /* a HIP runtime call failed; text in ag_last_error() */
+} ag_status;
+
+typedef enum { AG_F32 = 0, AG_BF16 = 1 } ag_dtype;
+
+/* Describes caller-owned device memory; plain data, read during the call only. */
+typedef struct {
+    void*   k_pool;            /* device, [num_pages][num_kv_heads][page_size][head_dim] */
+    void*   v_pool;            /* device, [num_pages][num_kv_heads][head_dim][page_size] */
+    int32_t num_pages;
+    int32_t page_size;
+    int32_t num_kv_heads;
+    int32_t head_dim;
+    int32_t dtype;             /* ag_dtype */
+} ag_kv_cache;
+
+/*
+ * KV append: the cache-building half of a prefill and the one token a decode
+ * step adds (paper Sec. II-A: the prefill "builds the KV cache"; Sec. III-C:
+ * the cache is shared by the prefill and decode sides).
+ * New token i of session s (row cu_new[s] + i of k_new / v_new) is written to
+ * logical position prefix_lens[s] + i for every KV head.  Bit-exact copy.
+ * total_new = cu_new[batch] is the host-side bound that sizes the launch.
+ * Two sessions appending to the same physical page is a caller error.
+ */
+AG_API ag_status ag_kv_append(const ag_kv_cache* cache,
+                       const void* k_new, const void* v_new,             /* device [T][Hkv][D] */
+                       const int32_t* block_tables, int32_t max_pages_per_seq,
+                       const int32_t* prefix_lens, const int32_t* new_lens,   /* device [B] */
+                       const int32_t* cu_new,                                 /* device [B+1] */
+                       int32_t batch, int32_t total_new, void* stream);
+
+/*
+ * Cold prefill (paper Sec. I, Sec. II-A): causal softmax attention of each
+ * session's N_s = new_lens[s] tokens over themselves, keys and values read
+ * back from the pages ag_kv_append has just written (prefix length 0):
+ *   O[t,h,:] = softmax_j<=i( scale * Q[t,h,:].K(s,h/G,j) ) . V(s,h/G,j),  t = cu_new[s] + i.
+ * max_new >= max_s new_lens[s] (host-side bound).  Sessions with N_s = 0
+ * contribute no rows.
+ */
+AG_API ag_status ag_attn_prefill(const ag_kv_cache* cache, const void* q, void* out,   /* device [T][Hq][D] */
+                          const int32_t* block_tables, int32_t max_pages_per_seq,
+                          const int32_t* new_lens, const int32_t* cu_new,
+                          int32_t batch, int32_t total_new, int32_t max_new,
+                          int32_t num_q_heads, float scale, void* stream);
+
+/*
+ * Resume prefill (paper Sec. I: later prefills append tool output to the
+ * cached context; Sec. II-A: prefix caching): row i of session s sits at
+ * logical position P_s + i, P_s = prefix_lens[s], and sees keys 0 .. P_s + i:
+ * the whole cached prefix plus the chunk up to itself.  The chunk's own K/V
+ * must already be appended.  With every P_s = 0 this is ag_attn_prefill.
+ * max_ctx >= max_s (P_s + N_s), and max_ctx <= max_pages_per_seq * page_size.
+ */
+AG_API ag_status ag_attn_resume(const ag_kv_cache* cache, const void* q, void* out,    /* device [T][Hq][D] */
+                         const int32_t* block_tables, int32_t max_pages_per_seq,
+                         const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* cu_new,
+                         int32_t batch, int32_t total_new, int32_t max_new, int32_t max_ctx,
+                         int32_t num_q_heads, float scale, void* stream);
+
+/*
+ * Short decode (paper Sec. II-A; Sec. III-B "decode steps": each active
+ * stream produces one token per step): one query per session over all
+ * ctx_lens[s] cached positions.  ctx_lens[s] COUNTS the step's own token,
+ * whose K/V must already be appended, so there is no mask and the result
+ * equals the last row of a prefill over the same ctx_lens[s] tokens.
+ * ctx_lens[s] = 0 gives a row of zeros.
+ * The context is cut into fixed-size splits handled by independent
+ * workgroups; their partial (max, sum, weighted values) triples go through
+ * `workspace` and are merged in a fixed order, so results are reproducible.
+ * workspace_bytes >= ag_attn_decode_workspace_bytes(batch, num_q_heads, head_dim, max_ctx).
+ */
+AG_API size_t    ag_attn_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t max_ctx);
+AG_API ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* out,    /* device [B][Hq][D] */
+                         const int32_t* block_tables, int32_t max_pages_per_seq,
+                         const int32_t* ctx_lens,                               /* device [B] */
+                         int32_t batch, int32_t max_ctx,
+                         int32_t num_q_heads, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * CU-masked streams: the counterpart of the paper's pre-created SM partitions
+ * (Sec. III-C; Algorithm 1 "partition SMs").  Kernels launched on the returned
+ * stream run only on the compute units whose bit is set.  cu_mask_words is a
+ * HOST array of n_words 32-bit words, bit b of word w = mask bit 32*w + b, in
+ * the order the HIP runtime defines for hipExtStreamCreateWithCUMask; at least
+ * one bit must be set.  The stream has default priority.  Destroy with
+ * ag_stream_destroy.  *stream_out is a hipStream_t.
+ */
+AG_API ag_status ag_stream_create_cumask(void** stream_out, const uint32_t* cu_mask_words, int32_t n_words);
+AG_API ag_status ag_stream_destroy(void* stream);
+
+/*
+ * Builds mask words (host) that select the same CUs in every XCD, so that a
+ * partition never empties one XCD: workgroups are dealt to XCDs round-robin,
+ * and mask bit b addresses XCD b % n_xcd, CU b / n_xcd of that XCD.  Sets the
+ * bits of CUs [first_cu_per_xcd, first_cu_per_xcd + cus_per_xcd) of each XCD;
+ * total_cus = n_xcd * (CUs per XCD).  Paper Eq. for the discrete allocation
+ * set {g, 2g, ..., S}: here g = n_xcd CUs.
+ */
+AG_API ag_status ag_cumask_build(uint32_t* words, int32_t n_words, int32_t total_cus, int32_t n_xcd,
+                          int32_t first_cu_per_xcd, int32_t cus_per_xcd);
+
+/*
+ * Measurement aid for the partition: launches n_workgroups one-wave
+ * workgroups on `stream`; each spins for about `spin_cycles` clock ticks so
+ * that the launch spreads over every CU the stream may use, then records
+ * where it ran.  ids_out (device, n_workgroups uint32): bits 0-7 the CU id
+ * within its shader array, 8-11 shader array, 12-15 shader engine, 16-19 XCD.
+ */
+AG_API ag_status ag_probe_placement(uint32_t* ids_out, int32_t n_workgroups, int32_t spin_cycles, void* stream);
+
+/* Device facts (host out-pointers, any may be NULL): CU count, XCD count if the runtime reports it else 0. */
+AG_API ag_status ag_device_info(int32_t* num_cus, int32_t* num_xcd, int32_t* wavefront_size, char* arch_name, int32_t arch_name_len);
+
+/*
+ * Synchronous checker for tests: copies the device-resident block tables and
+ * lengths to the host and verifies what the fast path assumes (page ids in
+ * range for every logical page in use, lengths within max_pages_per_seq *
+ * page_size, cu_new consistent).  prefix_lens or cu_new may be NULL.
+ * Synchronises `stream`.  Returns AG_ERR_INVALID_ARG with a message on the
+ * first violation.
+ */
+AG_API ag_status ag_debug_validate(const ag_kv_cache* cache, const int32_t* block_tables, int32_t max_pages_per_seq,
+                            const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* cu_new,
+                            int32_t batch, void* stream);
+
+AG_API const char* ag_status_string(ag_status s);
+AG_API const char* ag_last_error(void);       /* thread-local; valid until the next failing call on this thread */
+AG_API const char* ag_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AG_H */

@@ -1,0 +1,208 @@
+"""ctypes binding of libagattn.so: same names as include/ag.h, argument
+marshalling only.  Every step of the path runs in the HIP kernels behind the
+C ABI; tensors are torch CUDA (ROCm) tensors used as device memory.
+
+There is no fallback: if the library is missing or was not built, importing
+`lib()` raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libagattn.so")
+
+AG_OK, AG_ERR_INVALID_ARG, AG_ERR_UNSUPPORTED, AG_ERR_WORKSPACE, AG_ERR_HIP = 0, -1, -2, -3, -4
+AG_F32, AG_BF16 = 0, 1
+
+EXPORTS = [
+    "ag_kv_append", "ag_attn_prefill", "ag_attn_resume", "ag_attn_decode_workspace_bytes", "ag_attn_decode",
+    "ag_stream_create_cumask", "ag_stream_destroy", "ag_cumask_build", "ag_probe_placement", "ag_device_info",
+    "ag_debug_validate", "ag_status_string", "ag_last_error", "ag_version",
+]
+
+
+class AgError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{message} (status {status})")
+        self.status = status
+
+
+class ag_kv_cache(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("num_pages", C.c_int32),
+                ("page_size", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("dtype", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library (built in-tree by paper_2603_10342_amd/build.py).  Fails loudly."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_10342_amd.build` "
+                          "(or __graft_entry__.build()); there is no fallback path")
+    l = C.CDLL(LIB_PATH)
+    vp, i32, i32p, u32p = C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_uint32)
+    cp = C.POINTER(ag_kv_cache)
+    l.ag_kv_append.argtypes = [cp, vp, vp, i32p, i32, i32p, i32p, i32p, i32, i32, vp]
+    l.ag_attn_prefill.argtypes = [cp, vp, vp, i32p, i32, i32p, i32p, i32, i32, i32, i32, C.c_float, vp]
+    l.ag_attn_resume.argtypes = [cp, vp, vp, i32p, i32, i32p, i32p, i32p, i32, i32, i32, i32, i32, C.c_float, vp]
+    l.ag_attn_decode_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    l.ag_attn_decode_workspace_bytes.restype = C.c_size_t
+    l.ag_attn_decode.argtypes = [cp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp, C.c_size_t, vp]
+    l.ag_stream_create_cumask.argtypes = [C.POINTER(vp), u32p, i32]
+    l.ag_stream_destroy.argtypes = [vp]
+    l.ag_cumask_build.argtypes = [u32p, i32, i32, i32, i32, i32]
+    l.ag_probe_placement.argtypes = [vp, i32, i32, vp]
+    l.ag_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.c_char_p, i32]
+    l.ag_debug_validate.argtypes = [cp, i32p, i32, i32p, i32p, i32p, i32, vp]
+    for name in EXPORTS:
+        if name not in ("ag_attn_decode_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
+            getattr(l, name).restype = C.c_int
+    l.ag_status_string.argtypes = [C.c_int]
+    for name in ("ag_status_string", "ag_last_error", "ag_version"):
+        getattr(l, name).restype = C.c_char_p
+    _lib = l
+    return l
+
+
+def _check(status: int):
+    if status != AG_OK:
+        raise AgError(status, lib().ag_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device pointers must come from contiguous CUDA/ROCm tensors")
+    return t.data_ptr()
+
+
+def _i32(t: Optional[torch.Tensor]):
+    if t is not None and t.dtype != torch.int32:
+        raise TypeError("length arrays and block tables are int32")
+    return _ptr(t)
+
+
+def _stream(stream) -> Optional[int]:
+    """None -> torch's current stream; an int is a raw hipStream_t; a torch stream gives its handle."""
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def torch_dtype(dtype: int):
+    return torch.float32 if dtype == AG_F32 else torch.bfloat16
+
+
+class KVCache:
+    """Caller-owned paged pools plus the geometry the library needs (mirrors ag_kv_cache)."""
+
+    def __init__(self, num_pages: int, page_size: int, num_kv_heads: int, head_dim: int, dtype: int,
+                 device="cuda", fill: Optional[float] = None):
+        td = torch_dtype(dtype)
+        mk = torch.empty if fill is None else (lambda *a, **k: torch.full(*a, fill_value=fill, **k))
+        self.k_pool = mk((num_pages, num_kv_heads, page_size, head_dim), dtype=td, device=device)
+        self.v_pool = mk((num_pages, num_kv_heads, head_dim, page_size), dtype=td, device=device)
+        self.num_pages, self.page_size = num_pages, page_size
+        self.num_kv_heads, self.head_dim, self.dtype = num_kv_heads, head_dim, dtype
+
+    def c_struct(self) -> ag_kv_cache:
+        return ag_kv_cache(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.num_pages, self.page_size,
+                           self.num_kv_heads, self.head_dim, self.dtype)
+
+    def v_pool_token_major(self) -> torch.Tensor:
+        """The value pool viewed as [page][head][slot][d] (a transpose of the stored [d][slot])."""
+        return self.v_pool.transpose(2, 3)
+
+
+def ag_kv_append(cache: KVCache, k_new, v_new, block_tables, prefix_lens, new_lens, cu_new, total_new: int,
+                 stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_kv_append(C.byref(c), _ptr(k_new), _ptr(v_new), _i32(block_tables), block_tables.shape[1],
+                              _i32(prefix_lens), _i32(new_lens), _i32(cu_new), new_lens.shape[0], total_new,
+                              _stream(stream)))
+
+
+def ag_attn_prefill(cache: KVCache, q, out, block_tables, new_lens, cu_new, total_new: int, max_new: int,
+                    num_q_heads: int, scale: float, stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_attn_prefill(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
+                                 _i32(new_lens), _i32(cu_new), new_lens.shape[0], total_new, max_new, num_q_heads,
+                                 scale, _stream(stream)))
+
+
+def ag_attn_resume(cache: KVCache, q, out, block_tables, prefix_lens, new_lens, cu_new, total_new: int,
+                   max_new: int, max_ctx: int, num_q_heads: int, scale: float, stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_attn_resume(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
+                                _i32(prefix_lens), _i32(new_lens), _i32(cu_new), new_lens.shape[0], total_new,
+                                max_new, max_ctx, num_q_heads, scale, _stream(stream)))
+
+
+def ag_attn_decode_workspace_bytes(batch: int, num_q_heads: int, head_dim: int, max_ctx: int) -> int:
+    return int(lib().ag_attn_decode_workspace_bytes(batch, num_q_heads, head_dim, max_ctx))
+
+
+def ag_attn_decode(cache: KVCache, q, out, block_tables, ctx_lens, max_ctx: int, num_q_heads: int, scale: float,
+                   workspace: torch.Tensor, stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_attn_decode(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
+                                _i32(ctx_lens), ctx_lens.shape[0], max_ctx, num_q_heads, scale, _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ag_cumask_build(total_cus: int, n_xcd: int, first_cu_per_xcd: int, cus_per_xcd: int) -> list:
+    n_words = (total_cus + 31) // 32
+    words = (C.c_uint32 * n_words)()
+    _check(lib().ag_cumask_build(words, n_words, total_cus, n_xcd, first_cu_per_xcd, cus_per_xcd))
+    return list(words)
+
+
+def ag_stream_create_cumask(words: Sequence[int]) -> int:
+    arr = (C.c_uint32 * len(words))(*words)
+    out = C.c_void_p()
+    _check(lib().ag_stream_create_cumask(C.byref(out), arr, len(words)))
+    return int(out.value)
+
+
+def ag_stream_destroy(stream: int):
+    _check(lib().ag_stream_destroy(stream))
+
+
+def ag_probe_placement(ids_out: torch.Tensor, spin_cycles: int, stream=None):
+    if ids_out.dtype != torch.int32:
+        raise TypeError("ids_out is a 32-bit integer tensor")
+    _check(lib().ag_probe_placement(_ptr(ids_out), ids_out.numel(), spin_cycles, _stream(stream)))
+
+
+def ag_device_info() -> dict:
+    cus, xcd, wave = C.c_int32(), C.c_int32(), C.c_int32()
+    name = C.create_string_buffer(64)
+    _check(lib().ag_device_info(C.byref(cus), C.byref(xcd), C.byref(wave), name, 64))
+    return {"num_cus": cus.value, "num_xcd": xcd.value, "wavefront_size": wave.value, "arch": name.value.decode()}
+
+
+def ag_debug_validate(cache: KVCache, block_tables, prefix_lens, new_lens, cu_new, stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_debug_validate(C.byref(c), _i32(block_tables), block_tables.shape[1], _i32(prefix_lens),
+                                   _i32(new_lens), _i32(cu_new), new_lens.shape[0], _stream(stream)))
+
+
+def ag_version() -> str:
+    return lib().ag_version().decode()
+
+
+def ag_status_string(status: int) -> str:
+    return lib().ag_status_string(status).decode()

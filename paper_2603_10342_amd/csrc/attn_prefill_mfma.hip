@@ -1,0 +1,305 @@
+// Cold and resume prefill over a paged KV cache, bf16, head_dim 128, page 16
+// (paper Sec. I and Sec. II-A: a cold prefill is full causal attention over
+// the prompt; a resume prefill appends a chunk to a cached context, so row i
+// of a session with P cached tokens sees keys 0 .. P + i.  Cold is P = 0.)
+//
+// A dense contraction, bound by the matrix cores: 4 * D flop per visible
+// (query, key) pair and head.  One workgroup (4 waves) owns 128 consecutive
+// query rows of one (session, query head); each wave owns 32 rows and keeps
+// their Q in registers.  Keys and values are taken 64 at a time (4 pages),
+// staged through LDS (double buffered, one barrier per tile):
+//
+//   S^T[key][query] = K[key][:] . Q[query][:]      2 x 8 MFMA 32x32x16
+//   streaming softmax per query column (running max / sum, exp2)
+//   O^T[d][query]  += V^T[d][key] . P^T[key][query]  4 x 4 MFMA 32x32x16
+//
+// Computing the transposed score tile puts one query in one lane (plus its
+// partner lane + 32), so the row max / sum need a single cross-lane step,
+// and the 8 scores a lane holds for one k-step of the second product are
+// already the B operand: P never leaves registers.  V pages are stored
+// transposed ([d][slot]); the copy into LDS orders the keys of each 16-byte
+// chunk to match that operand.  Both LDS tiles are XOR-swizzled by row so
+// the 16-byte operand reads are conflict free.
+//
+// Tiles wholly above a wave's rows are skipped; only tiles that straddle the
+// diagonal are masked.  Workgroups are numbered so that the XCD a workgroup
+// lands on (id % 8) owns a contiguous range of KV heads, keeping a session's
+// K/V for that head in one L2, and within it the longest query tiles go first.
+#include <atomic>
+
+#include "ag_internal.h"
+
+namespace ag {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int D = 128;
+constexpr int PS = 16;
+constexpr int BM = 128;                 // query rows per workgroup
+constexpr int BN = 64;                  // keys per tile
+constexpr int kTileBytes = BN * D * 2;  // 16 KiB, for K and for V^T alike
+constexpr int kLdsBytes = 4 * kTileBytes;
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ u32x4 ld16g(const __bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
+
+__device__ __forceinline__ u32x4 keep_first(u32x4 u, int keep)
+{
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const uint32_t lo = (2 * w < keep) ? 0x0000FFFFu : 0u;
+        const uint32_t hi = (2 * w + 1 < keep) ? 0xFFFF0000u : 0u;
+        u[w] &= (lo | hi);
+    }
+    return u;
+}
+
+struct Stage {          // one thread's share of a K tile and a V tile on its way to LDS
+    u32x4 k[4];
+    u32x4 v[4];
+};
+
+__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_tiles, int per_xcd, int64_t total_work)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+
+    // ---- which (session, head, query tile) ----
+    const int xcd = blockIdx.x & 7, ord = blockIdx.x >> 3;
+    const int64_t wk = (int64_t)xcd * per_xcd + ord;
+    if (wk >= total_work) return;
+    const int hkv = a.c.hkv, hq = a.hq, G = hq / hkv;
+    const int inner = a.batch * G;
+    const int g = (int)(wk / ((int64_t)q_tiles * inner));
+    const int rem = (int)(wk % ((int64_t)q_tiles * inner));
+    const int qt = q_tiles - 1 - rem / inner;
+    const int s = (rem % inner) / G;
+    const int h = g * G + (rem % inner) % G;
+
+    const int N = a.new_lens[s];
+    const int q0 = qt * BM;
+    if (q0 >= N) return;
+    const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
+    const int ctx = P + N;
+    const int64_t t_base = (int64_t)a.cu_new[s] + q0;
+
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int n = lane & 31, hi = lane >> 5;
+    const int rows_wg = min(BM, N - q0);            // valid query rows of this workgroup
+    const int qrow0 = 32 * w;                       // first row of this wave inside the tile
+    const int rows_w = max(0, min(32, rows_wg - qrow0));
+
+    const int n_tiles = (P + q0 + rows_wg - 1) / BN + 1;
+    const int wave_tiles = rows_w > 0 ? (P + q0 + qrow0 + rows_w - 1) / BN + 1 : 0;
+    const int first_masked = (P + q0 + qrow0 + 1) / BN;   // first tile holding a key this wave's row 0 may not see
+
+    const __bf16* kpool = (const __bf16*)a.c.k;
+    const __bf16* vpool = (const __bf16*)a.c.v;
+    const int32_t* bt = a.bt + (int64_t)s * a.max_pages;
+    const int last_page = (ctx - 1) >> 4;
+
+    // ---- Q^T as B operand: column n = query row, k-step ks covers channels ks*16 + hi*8 .. +7 ----
+    bf16x8 qf[8];
+    {
+        const int row = min(qrow0 + n, rows_wg - 1);
+        const __bf16* qp = (const __bf16*)a.q + ((t_base + row) * hq + h) * D + hi * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
+    }
+
+    // ---- copy roles ----
+    const int kc = tid & 15, kslot = tid >> 4;      // K: chunk of 8 channels, slot; pages 0..3 of the tile
+    const int vd = tid & 127, vpg0 = tid >> 7;      // V: channel row, pages vpg0 and vpg0 + 2
+
+    auto load_tile = [&](int t, Stage& st) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t page = bt[min(t * 4 + i, last_page)];
+            st.k[i] = ld16g(kpool + ((page * hkv + g) * PS + kslot) * D + kc * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = vpg0 + 2 * i;
+            const int64_t page = bt[min(t * 4 + j, last_page)];
+            const __bf16* vp = vpool + ((page * hkv + g) * D + vd) * PS;
+            u32x4 lo = ld16g(vp), hi8 = ld16g(vp + 8);
+            const int keep = ctx - (t * BN + j * PS);           // slots < keep hold real tokens
+            if (keep < PS) {                                    // unwritten slots may hold anything
+                lo = keep_first(lo, keep);
+                hi8 = keep_first(hi8, keep - 8);
+            }
+            // chunk (j, 0) = slots 0-3, 8-11; chunk (j, 1) = slots 4-7, 12-15
+            st.v[2 * i] = u32x4{lo[0], lo[1], hi8[0], hi8[1]};
+            st.v[2 * i + 1] = u32x4{lo[2], lo[3], hi8[2], hi8[3]};
+        }
+    };
+    auto store_tile = [&](int buf, const Stage& st) {
+        unsigned char* kb = lds + buf * 2 * kTileBytes;
+        unsigned char* vb = kb + kTileBytes;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int key = i * PS + kslot;
+            *reinterpret_cast<u32x4*>(kb + key * 256 + ((kc ^ (key & 15)) << 4)) = st.k[i];
+        }
+        const int sw = (vd >> 1) & 7;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int j = vpg0 + 2 * i;
+            *reinterpret_cast<u32x4*>(vb + vd * 128 + (((j * 2) ^ sw) << 4)) = st.v[2 * i];
+            *reinterpret_cast<u32x4*>(vb + vd * 128 + (((j * 2 + 1) ^ sw) << 4)) = st.v[2 * i + 1];
+        }
+    };
+
+    const float sl2 = a.scale * kLog2e;
+    float m = -INFINITY, lsum = 0.f;
+    f32x16 o[4];
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
+
+    Stage stg;
+    load_tile(0, stg);
+    store_tile(0, stg);
+    __syncthreads();
+
+    const int qpos = P + q0 + qrow0 + n;            // logical position of this lane's query
+
+#pragma unroll 1
+    for (int t = 0; t < n_tiles; ++t) {
+        const bool more = t + 1 < n_tiles;
+        if (more) load_tile(t + 1, stg);
+
+        if (t < wave_tiles) {
+            const unsigned char* kb = lds + (t & 1) * 2 * kTileBytes;
+            const unsigned char* vb = kb + kTileBytes;
+            f32x16 sc[2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sc[b][i] = 0.f;
+                const int key = b * 32 + n;
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) {
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kb + key * 256 + (((ks * 2 + hi) ^ (key & 15)) << 4));
+                    sc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sc[b], 0, 0, 0);
+                }
+            }
+            // sc[b][i] is key t*64 + b*32 + (i/4)*8 + hi*4 + i%4 against query n
+            float mx = -INFINITY;
+            if (t >= first_masked) {
+                const int kbase = t * BN + hi * 4;
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kbase + b * 32 + (i >> 2) * 8 + (i & 3);
+                        sc[b][i] = key <= qpos ? sc[b][i] * sl2 : -INFINITY;
+                    }
+            } else {
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sc[b][i] *= sl2;
+            }
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sc[b][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx);       // finite from tile 0 on: key 0 is visible to every row
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            float psum = 0.f;
+            bf16x8 pb[4];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float p = __builtin_amdgcn_exp2f(sc[b][i] - m_new);
+                    psum += p;
+                    pb[b * 2 + (i >> 3)][i & 7] = (__bf16)p;
+                }
+            lsum = lsum * alpha + psum;
+            m = m_new;
+#pragma unroll
+            for (int mb = 0; mb < 4; ++mb) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
+                const int d = mb * 32 + n;
+                const int sw = (d >> 1) & 7;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const bf16x8 va = *reinterpret_cast<const bf16x8*>(vb + d * 128 + (((j * 2 + hi) ^ sw) << 4));
+                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j], o[mb], 0, 0, 0);
+                }
+            }
+        }
+
+        if (more) store_tile((t + 1) & 1, stg);
+        __syncthreads();
+    }
+
+    // ---- normalise, transpose through LDS, store rows contiguously ----
+    lsum += __shfl_xor(lsum, 32);
+    const float inv = 1.0f / lsum;
+    unsigned char* ob = lds + w * (32 * 256);       // this wave's [32 rows][128 ch] bf16, rows XOR-swizzled
+    // (the barrier that closed the loop guarantees nobody still reads the K/V tiles)
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+            bf16x4 x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[mb][q4 * 4 + e] * inv);
+            const int d = mb * 32 + q4 * 8 + hi * 4;            // 4 consecutive channels
+            const int chunk = d >> 3;
+            *reinterpret_cast<bf16x4*>(ob + n * 256 + ((chunk ^ (n & 15)) << 4) + (d & 7) * 2) = x;
+        }
+    __syncthreads();
+    {
+        const int c = lane & 15;
+        __bf16* outp = (__bf16*)a.out;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int row = (lane >> 4) + 4 * k;
+            if (row < rows_w) {
+                const u32x4 x = *reinterpret_cast<const u32x4*>(ob + row * 256 + ((c ^ (row & 15)) << 4));
+                *reinterpret_cast<u32x4*>(outp + ((t_base + qrow0 + row) * hq + h) * D + c * 8) = x;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+bool prefill_mfma_supported(const AttnArgs& a)
+{
+    return a.c.dtype == AG_BF16 && a.c.d == D && a.c.ps == PS &&
+           (((uintptr_t)a.q | (uintptr_t)a.out | (uintptr_t)a.c.k | (uintptr_t)a.c.v) % 16 == 0);
+}
+
+ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
+{
+    static std::atomic<bool> attr_set{false};
+    if (!attr_set.load()) {
+        ag_status e = hip_check(hipFuncSetAttribute((const void*)prefill_mfma_kernel,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
+                                "hipFuncSetAttribute(prefill)");
+        if (e) return e;
+        attr_set.store(true);
+    }
+    const int q_tiles = (a.max_new + BM - 1) / BM;
+    const int64_t total = (int64_t)a.batch * a.hq * q_tiles;
+    const int64_t per_xcd = (total + 7) / 8;
+    if (per_xcd * 8 > 0x7fffffff) { set_error("too many query tiles for one launch"); return AG_ERR_INVALID_ARG; }
+    hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), kLdsBytes, st, a, q_tiles,
+                       (int)per_xcd, total);
+    return hip_check(hipGetLastError(), "prefill launch");
+}
+
+}  // namespace ag
