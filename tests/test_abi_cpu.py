@@ -1,0 +1,88 @@
+"""No GPU needed: the C-ABI library loads, exports every symbol include/ag.h
+declares, and its host-side checks answer before any device work."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2603_10342_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "ag.h")).read()
+    return sorted(set(re.findall(r"AG_API\s+[\w\s\*]+?\b(ag_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 14 and "ag_attn_decode" in names and "ag_stream_create_cumask" in names
+    assert sorted(B.EXPORTS) == names
+    l = B.lib()
+    for n in names:
+        assert hasattr(l, n), n
+
+
+def test_status_strings_and_version():
+    assert B.ag_status_string(0) == "AG_OK"
+    assert B.ag_status_string(-3) == "AG_ERR_WORKSPACE"
+    assert "gfx950" in B.ag_version()
+
+
+def test_null_and_shape_errors_come_from_the_host_layer():
+    l = B.lib()
+    ok = B.ag_kv_cache(1, 1, 8, 16, 2, 128, B.AG_BF16)          # non-null fake pointers: never dereferenced here
+    assert l.ag_kv_append(None, None, None, None, 1, None, None, None, 1, 1, None) == B.AG_ERR_INVALID_ARG
+    assert l.ag_kv_append(C.byref(ok), None, None, None, 1, None, None, None, 1, 1, None) == B.AG_ERR_INVALID_ARG
+    assert b"NULL" in l.ag_last_error()
+    for field, val, want in [("dtype", 7, B.AG_ERR_UNSUPPORTED), ("head_dim", 100, B.AG_ERR_UNSUPPORTED),
+                             ("head_dim", 512, B.AG_ERR_UNSUPPORTED), ("page_size", 24, B.AG_ERR_UNSUPPORTED),
+                             ("num_pages", 0, B.AG_ERR_INVALID_ARG)]:
+        c = B.ag_kv_cache(1, 1, 8, 16, 2, 128, B.AG_BF16)
+        setattr(c, field, val)
+        assert l.ag_attn_prefill(C.byref(c), 1, 1, 1, 4, 1, 1, 1, 16, 16, 4, 0.1, None) == want, field
+    # heads not a multiple, contradictory bounds, bad scale
+    assert l.ag_attn_prefill(C.byref(ok), 16, 16, 16, 4, 16, 16, 1, 16, 16, 3, 0.1, None) == B.AG_ERR_INVALID_ARG
+    assert l.ag_attn_prefill(C.byref(ok), 16, 16, 16, 4, 16, 16, 1, 16, 32, 4, 0.1, None) == B.AG_ERR_INVALID_ARG
+    assert l.ag_attn_prefill(C.byref(ok), 16, 16, 16, 4, 16, 16, 1, 16, 16, 4, 0.0, None) == B.AG_ERR_INVALID_ARG
+    assert l.ag_attn_resume(C.byref(ok), 16, 16, 16, 4, 16, 16, 16, 1, 16, 16, 65, 4, 0.1, None) == B.AG_ERR_INVALID_ARG
+    assert l.ag_attn_decode(C.byref(ok), 16, 16, 16, 4, 16, 1, 64, 4, 0.1, 16, 8, None) == B.AG_ERR_WORKSPACE
+    assert l.ag_attn_decode(C.byref(ok), 16, 16, 16, 4, 16, 1, 65, 4, 0.1, 16, 1 << 20, None) == B.AG_ERR_INVALID_ARG
+    # zero new tokens is a no-op that never reaches the device
+    assert l.ag_kv_append(C.byref(ok), 16, 16, 16, 4, 16, 16, 16, 1, 0, None) == B.AG_OK
+    assert l.ag_attn_prefill(C.byref(ok), 16, 16, 16, 4, 16, 16, 1, 0, 0, 4, 0.1, None) == B.AG_OK
+
+
+def test_decode_workspace_size():
+    # one (max, sum, D values) fp32 triple per (session, query head, 512-token split)
+    assert B.ag_attn_decode_workspace_bytes(64, 32, 128, 4096) == 64 * 32 * 8 * 130 * 4
+    assert B.ag_attn_decode_workspace_bytes(2, 4, 64, 1) == 2 * 4 * 1 * 66 * 4
+    assert B.ag_attn_decode_workspace_bytes(0, 4, 64, 1) == 0
+
+
+def test_cumask_builder_is_symmetric_over_xcds():
+    w = B.ag_cumask_build(256, 8, 0, 4)                 # 4 CUs in each of 8 XCDs = 32 CUs
+    assert w == [0xFFFFFFFF] + [0] * 7
+    w = B.ag_cumask_build(256, 8, 4, 28)                # the complement
+    assert w == [0] + [0xFFFFFFFF] * 7
+    w = B.ag_cumask_build(256, 8, 0, 12)
+    assert sum(bin(x).count("1") for x in w) == 96
+    bits = [i for i in range(256) if (w[i // 32] >> (i % 32)) & 1]
+    assert all(sum(1 for b in bits if b % 8 == x) == 12 for x in range(8))
+    w = B.ag_cumask_build(64, 4, 1, 2)                  # other shapes: bit = cu * n_xcd + xcd
+    assert [i for i in range(64) if (w[i // 32] >> (i % 32)) & 1] == [4, 5, 6, 7, 8, 9, 10, 11]
+    with pytest.raises(B.AgError):
+        B.ag_cumask_build(256, 8, 30, 4)
+    with pytest.raises(B.AgError):
+        B.ag_cumask_build(250, 8, 0, 4)
+
+
+def test_empty_mask_is_rejected_without_touching_the_device():
+    l = B.lib()
+    words = (C.c_uint32 * 8)()
+    out = C.c_void_p()
+    assert l.ag_stream_create_cumask(C.byref(out), words, 8) == B.AG_ERR_INVALID_ARG
+    assert l.ag_stream_create_cumask(None, words, 8) == B.AG_ERR_INVALID_ARG
+    assert l.ag_stream_destroy(None) == B.AG_ERR_INVALID_ARG
