@@ -1,0 +1,417 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-KV attention hot path on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads decode,cold,resume,mixed]
+
+Prints ONE JSON line.  The headline metric is decode-attention HBM GB/s on the
+decode-only configuration (64 sessions, contexts U[1024, 4096], 32/8 heads,
+head_dim 128, page 16, bf16).  A step is one pass of the decode path over the
+batch: ag_kv_append of the step's token for every session, then
+ag_attn_decode.  The same line carries the two prefill configurations
+(TFLOP/s against the dense bf16 MFMA peak), the mixed-load decode-step
+percentiles under CU-masked streams, and the fp64 oracle timed on the host.
+
+All inputs are synthetic and seeded (paper_2603_10342_amd/inputs.py) and are
+resident in HBM before any timed region starts.  Throughput figures count
+ALGORITHMIC bytes / flops only (every cached K/V byte once; 4*D flop per
+visible query-key pair and head).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import threading
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def pct(xs, p):
+    """Nearest-rank percentile."""
+    s = sorted(xs)
+    k = max(0, min(len(s) - 1, int(np.ceil(p / 100.0 * len(s))) - 1))
+    return s[k]
+
+
+class Dev:
+    """A seeded Batch moved to the device once."""
+
+    def __init__(self, b, torch, dev="cuda"):
+        from paper_2603_10342_amd import inputs as I
+        g = b.geom
+
+        def t(a):
+            if g.dtype == I.F32:
+                return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).to(dev).view(torch.bfloat16)
+
+        def i32(a):
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+
+        self.b, self.g = b, g
+        self.q, self.k_new, self.v_new = t(b.q), t(b.k_new), t(b.v_new)
+        self.bt, self.prefix, self.new, self.cu, self.ctx = (i32(b.block_tables), i32(b.prefix_lens), i32(b.new_lens),
+                                                             i32(b.cu_new), i32(b.ctx_lens))
+        self.total = b.total_new
+        self.max_new = int(b.new_lens.max())
+        self.max_ctx = int(b.ctx_lens.max())
+        self.out = torch.zeros_like(self.q)
+        self.i32 = i32
+
+
+def time_steps(torch, step, steps, warmup, stream=None):
+    """W untimed steps, then exactly K steps between two synchronisations.  Returns seconds per step."""
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        step(warmup + i)
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def kernel_time(B, torch, step, steps, warmup):
+    """Mean duration (us) of the main attention kernel, from HIP events recorded around each launch on its stream."""
+    B.ag_prof_enable(steps)
+    try:
+        for i in range(warmup):
+            step(i)
+        torch.cuda.synchronize()
+        B.ag_prof_collect()
+        for i in range(steps):
+            step(warmup + i)
+        torch.cuda.synchronize()
+        return B.ag_prof_collect()
+    finally:
+        B.ag_prof_disable()
+
+
+# --------------------------------------------------------------------------- decode (config 2)
+def bench_decode(args, torch, B, I):
+    c = I.make_decode()
+    g = c.geom
+    nb = len(c.ctx_lens)
+    fill, step = Dev(c.fill, torch), Dev(c.step, torch)
+    ctx = step.ctx
+    max_ctx = int(c.ctx_lens.max())
+    sets = []
+    for r in range(args.sets):
+        bt = c.block_tables if r == 0 else I.deal_block_tables(I.rng_for(I.config_seed(2), 100 + r), c.ctx_lens,
+                                                                g.page_size, g.num_pages, c.block_tables.shape[1])
+        cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+        btd = fill.i32(bt)
+        B.ag_kv_append(cache, fill.k_new, fill.v_new, btd, fill.prefix, fill.new, fill.cu, fill.total)
+        sets.append((cache, btd))
+    ws = torch.empty(B.ag_attn_decode_workspace_bytes(nb, g.num_q_heads, g.head_dim, max_ctx) // 4,
+                     dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+
+    def one(i):
+        cache, btd = sets[i % len(sets)]
+        B.ag_kv_append(cache, step.k_new, step.v_new, btd, step.prefix, step.new, step.cu, step.total)
+        B.ag_attn_decode(cache, step.q, step.out, btd, ctx, max_ctx, g.num_q_heads, g.scale, ws)
+
+    sec = time_steps(torch, one, args.steps, args.warmup)
+    prof = kernel_time(B, torch, one, args.steps, args.warmup)
+
+    esz = 2
+    kv_bytes = int(c.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
+    qo_bytes = 2 * nb * g.num_q_heads * g.head_dim * esz
+    bt_bytes = int(((c.ctx_lens + g.page_size - 1) // g.page_size).sum()) * 4
+    attn_bytes = kv_bytes + qo_bytes + bt_bytes
+    append_bytes = 2 * nb * g.kv_bytes_per_token
+    out = {
+        "ms_per_step": sec * 1e3,
+        "step_GBps": (attn_bytes + append_bytes) / sec / 1e9,
+        "attn_bytes": attn_bytes, "append_bytes": append_bytes, "kv_bytes": kv_bytes,
+        "kernel": "decode_split_kernel", "kernel_us": prof["mean_us"], "kernel_us_min": prof["min_us"],
+        "kernel_GBps": attn_bytes / (prof["mean_us"] * 1e-6) / 1e9,
+        "sets": len(sets), "sessions": nb, "mean_ctx": float(c.ctx_lens.mean()),
+    }
+    log("decode", json.dumps(out))
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O       # cpu_baseline leg: the only use of the oracle in this file
+        kp, vp = I.zero_pool(g.pool_shape, g.dtype), I.zero_pool(g.pool_shape, g.dtype)
+        for b in (c.fill, c.step):
+            O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
+        reps, t_cpu, ref = 0, 0.0, None
+        while t_cpu < 10.0 and reps < 20:
+            t0 = time.perf_counter()
+            ref = O.decode(kp, vp, g.dtype, c.step.q, c.block_tables, c.ctx_lens, g.num_q_heads, g.scale)
+            t_cpu += time.perf_counter() - t0
+            reps += 1
+        cache, btd = sets[0]
+        one(0)
+        torch.cuda.synchronize()
+        got = I.stored_to_f64(step.out.view(torch.int16).cpu().numpy().view(np.uint16), g.dtype)
+        err = np.abs(got - ref)
+        out["cpu_baseline"] = {"value": attn_bytes / (t_cpu / reps) / 1e9, "unit": "GB/s", "cores": O.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"the whole decode batch (64 sessions), {reps} repetitions, {t_cpu:.1f} s"}
+        out["check_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                                  "rel_fro": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+        log("decode cpu", json.dumps(out["cpu_baseline"]), json.dumps(out["check_vs_oracle"]))
+        del kp, vp
+    return out
+
+
+# --------------------------------------------------------------------------- prefill (configs 3, 4)
+def bench_prefill(kind, args, torch, B, I):
+    steps, warmup = max(5, args.steps // 10), max(2, args.warmup // 5)
+    if kind == "cold":
+        b = I.make_cold()
+        g = b.geom
+        cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+        d = Dev(b, torch)
+    else:
+        c = I.make_resume()
+        b, g = c.chunk, c.geom
+        cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+        f = Dev(c.fill, torch)
+        B.ag_kv_append(cache, f.k_new, f.v_new, f.bt, f.prefix, f.new, f.cu, f.total)
+        d = Dev(b, torch)
+        del f
+    torch.cuda.synchronize()
+
+    def one(i):
+        B.ag_kv_append(cache, d.k_new, d.v_new, d.bt, d.prefix, d.new, d.cu, d.total)
+        if kind == "cold":
+            B.ag_attn_prefill(cache, d.q, d.out, d.bt, d.new, d.cu, d.total, d.max_new, g.num_q_heads, g.scale)
+        else:
+            B.ag_attn_resume(cache, d.q, d.out, d.bt, d.prefix, d.new, d.cu, d.total, d.max_new, d.max_ctx,
+                             g.num_q_heads, g.scale)
+
+    sec = time_steps(torch, one, steps, warmup)
+    prof = kernel_time(B, torch, one, steps, warmup)
+    flops = b.attn_flops()
+    out = {
+        "ms_per_step": sec * 1e3, "steps": steps, "warmup": warmup,
+        "step_TFLOPs": flops / sec / 1e12, "tokens_per_s": b.total_new / sec,
+        "flops": flops, "tokens": b.total_new, "sessions": b.batch,
+        "kernel": "prefill_mfma_kernel", "kernel_us": prof["mean_us"], "kernel_us_min": prof["min_us"],
+        "kernel_TFLOPs": flops / (prof["mean_us"] * 1e-6) / 1e12,
+        "roofline": {"bound": "mfma", "achieved": flops / (prof["mean_us"] * 1e-6) / 1e12,
+                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": flops / (prof["mean_us"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+    }
+    log(kind, json.dumps(out))
+
+    if kind == "cold" and not args.no_cpu_baseline:
+        from oracle import oracle as O       # cpu_baseline leg
+        kp, vp = I.zero_pool(g.pool_shape, g.dtype), I.zero_pool(g.pool_shape, g.dtype)
+        O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
+        rng = I.rng_for(I.config_seed(3), 77)
+        n_rows = 256
+        rs = rng.integers(0, b.batch, size=n_rows).astype(np.int32)
+        ri = rng.integers(0, 4096, size=n_rows).astype(np.int32)
+        t0 = time.perf_counter()
+        ref = O.attn(kp, vp, g.dtype, b.q, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new, g.num_q_heads,
+                     g.scale, rows=(rs, ri))
+        t_cpu = time.perf_counter() - t0
+        fl = 4 * g.head_dim * g.num_q_heads * int((ri.astype(np.int64) + 1).sum())
+        one(0)
+        torch.cuda.synchronize()
+        rows = torch.from_numpy(b.cu_new[rs].astype(np.int64) + ri).to("cuda")
+        got = I.stored_to_f64(d.out[rows].contiguous().view(torch.int16).cpu().numpy().view(np.uint16), g.dtype)
+        err = np.abs(got - ref)
+        out["cpu_baseline"] = {"value": fl / t_cpu / 1e12, "unit": "TFLOP/s", "cores": O.num_threads(),
+                               "kind": "oracle", "sample": f"{n_rows} random query rows x 32 heads, {t_cpu:.1f} s"}
+        out["check_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                                  "rel_fro": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+        log("cold cpu", json.dumps(out["cpu_baseline"]), json.dumps(out["check_vs_oracle"]))
+    return out
+
+
+# --------------------------------------------------------------------------- mixed load (config 5)
+def placement(torch, B, stream, n_wg=4096):
+    """Which (XCD, CU) pairs does a stream's work land on?"""
+    ids = torch.zeros(n_wg, dtype=torch.int32, device="cuda")
+    B.ag_probe_placement(ids, 20000, stream)
+    torch.cuda.synchronize()
+    v = ids.cpu().numpy().astype(np.int64)
+    cu = (v & 0xFF) | (((v >> 8) & 0xF) << 8) | (((v >> 12) & 0xF) << 12)
+    xcd = (v >> 16) & 0xF
+    pairs = set(zip(xcd.tolist(), cu.tolist()))
+    per_xcd = {}
+    for x, _ in pairs:
+        per_xcd[x] = per_xcd.get(x, 0) + 1
+    return pairs, per_xcd
+
+
+def bench_mixed(args, torch, B, I, info):
+    m = I.make_mixed()
+    g = m.geom
+    cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+    cold, rfill, res, dfill, dec = (Dev(x, torch) for x in (m.cold, m.resume_fill, m.resume, m.decode_fill, m.decode))
+    for f in (rfill, dfill):
+        B.ag_kv_append(cache, f.k_new, f.v_new, f.bt, f.prefix, f.new, f.cu, f.total)
+    nb = dec.b.batch
+    max_ctx = dec.max_ctx
+    ws = torch.empty(B.ag_attn_decode_workspace_bytes(nb, g.num_q_heads, g.head_dim, max_ctx) // 4,
+                     dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    total_cus = info["num_cus"]
+    n_xcd = info["num_xcd"] or 8
+    per = total_cus // n_xcd
+    prefill_tokens = cold.total + res.total
+    prefill_flops = m.cold.attn_flops() + m.resume.attn_flops()
+    kv_bytes = int(m.decode.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
+
+    def decode_step(st):
+        B.ag_kv_append(cache, dec.k_new, dec.v_new, dec.bt, dec.prefix, dec.new, dec.cu, dec.total, stream=st)
+        B.ag_attn_decode(cache, dec.q, dec.out, dec.bt, dec.ctx, max_ctx, g.num_q_heads, g.scale, ws, stream=st)
+
+    def prefill_loop(st):
+        B.ag_kv_append(cache, cold.k_new, cold.v_new, cold.bt, cold.prefix, cold.new, cold.cu, cold.total, stream=st)
+        B.ag_attn_prefill(cache, cold.q, cold.out, cold.bt, cold.new, cold.cu, cold.total, cold.max_new,
+                          g.num_q_heads, g.scale, stream=st)
+        B.ag_kv_append(cache, res.k_new, res.v_new, res.bt, res.prefix, res.new, res.cu, res.total, stream=st)
+        B.ag_attn_resume(cache, res.q, res.out, res.bt, res.prefix, res.new, res.cu, res.total, res.max_new,
+                         res.max_ctx, g.num_q_heads, g.scale, stream=st)
+
+    def run(dstream, pstream, steps, warm=100):
+        """Decode steps (one host sync each, as a real decode loop has) with an optional prefill loop beside."""
+        ds = torch.cuda.ExternalStream(dstream) if dstream else torch.cuda.current_stream()
+        stop = threading.Event()
+        loops = [0]
+        t_pref = [0.0]
+
+        def pre():
+            ps = torch.cuda.ExternalStream(pstream)
+            t0 = time.perf_counter()
+            while not stop.is_set():
+                prefill_loop(pstream)
+                ps.synchronize()
+                loops[0] += 1
+            t_pref[0] = time.perf_counter() - t0
+
+        th = None
+        if pstream is not None:
+            th = threading.Thread(target=pre)
+            th.start()
+            time.sleep(0.05)
+        lat = []
+        for i in range(warm + steps):
+            t0 = time.perf_counter()
+            decode_step(dstream)
+            ds.synchronize()
+            if i >= warm:
+                lat.append((time.perf_counter() - t0) * 1e6)
+        stop.set()
+        if th:
+            th.join()
+        r = {"p50_us": pct(lat, 50), "p99_us": pct(lat, 99), "mean_us": float(np.mean(lat)), "steps": steps}
+        if th and t_pref[0] > 0:
+            r["prefill_tokens_per_s"] = loops[0] * prefill_tokens / t_pref[0]
+            r["prefill_TFLOPs"] = loops[0] * prefill_flops / t_pref[0] / 1e12
+            r["prefill_loops"] = loops[0]
+        return r
+
+    old_si = sys.getswitchinterval()
+    sys.setswitchinterval(1e-5)
+    out = {"decode_kv_bytes_per_step": kv_bytes, "prefill_tokens_per_loop": prefill_tokens,
+           "prefill_flops_per_loop": prefill_flops, "splits": {}}
+    try:
+        out["decode_alone_full_gpu"] = run(None, None, args.mixed_steps)
+        plain_a = B.ag_stream_create_cumask([0xFFFFFFFF] * ((total_cus + 31) // 32))
+        plain_b = B.ag_stream_create_cumask([0xFFFFFFFF] * ((total_cus + 31) // 32))
+        out["unmasked_two_streams"] = run(plain_a, plain_b, args.mixed_steps)
+        for cus in (32, 64, 96):
+            k = cus // n_xcd
+            sd = B.ag_stream_create_cumask(B.ag_cumask_build(total_cus, n_xcd, 0, k))
+            sp = B.ag_stream_create_cumask(B.ag_cumask_build(total_cus, n_xcd, k, per - k))
+            pd, pxd = placement(torch, B, sd)
+            pp, pxp = placement(torch, B, sp)
+            alone = run(sd, None, args.mixed_steps)
+            mixed = run(sd, sp, args.mixed_steps)
+            out["splits"][str(cus)] = {
+                "decode_cus_seen": len(pd), "prefill_cus_seen": len(pp), "overlap": len(pd & pp),
+                "decode_cus_per_xcd": sorted(pxd.values()), "prefill_cus_per_xcd": sorted(pxp.values()),
+                "decode_alone": alone, "with_prefill": mixed,
+                "p99_ratio": mixed["p99_us"] / alone["p99_us"], "p50_ratio": mixed["p50_us"] / alone["p50_us"],
+            }
+            log("mixed", cus, json.dumps(out["splits"][str(cus)]))
+            B.ag_stream_destroy(sd)
+            B.ag_stream_destroy(sp)
+        B.ag_stream_destroy(plain_a)
+        B.ag_stream_destroy(plain_b)
+    finally:
+        sys.setswitchinterval(old_si)
+    log("mixed", json.dumps({k: v for k, v in out.items() if k != "splits"}))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workloads", default="decode,cold,resume,mixed")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sets", type=int, default=4, help="disjoint session sets the decode step rotates over")
+    ap.add_argument("--mixed-steps", type=int, default=1000)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only; run with --gpus 1 (the path shards by session or "
+              "by KV head with no exchange between GPUs, so a multi-GPU figure would be N independent copies)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_10342_amd import binding as B
+    from paper_2603_10342_amd import inputs as I
+
+    torch.cuda.set_device(0)
+    info = B.ag_device_info()
+    log("device", info, B.ag_version())
+    want = [w for w in args.workloads.split(",") if w]
+    res = {}
+    if "decode" in want:
+        res["decode"] = bench_decode(args, torch, B, I)
+    if "cold" in want:
+        res["cold_prefill"] = bench_prefill("cold", args, torch, B, I)
+    if "resume" in want:
+        res["resume_prefill"] = bench_prefill("resume", args, torch, B, I)
+    if "mixed" in want:
+        res["mixed"] = bench_mixed(args, torch, B, I, info)
+
+    d = res.get("decode")
+    line = {
+        "metric": "decode_attn_hbm_GBps", "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "decode-only batch: 64 sessions, ctx ~ U[1024,4096], 32 q heads / 8 kv heads, "
+                               "head_dim 128, page 16, 32768-page pool; step = ag_kv_append(1 token/session) + ag_attn_decode",
+                   "sessions": 64, "num_q_heads": 32, "num_kv_heads": 8, "head_dim": 128, "page_size": 16,
+                   "rotating_session_sets": args.sets},
+        "device": info,
+    }
+    if d:
+        line.update({
+            "value": d["step_GBps"], "ms_per_step": d["ms_per_step"],
+            "roofline": {"bound": "hbm", "achieved": d["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                         "frac": d["kernel_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                         "kernel": d["kernel"], "kernel_us": d["kernel_us"], "algorithmic_bytes": d["attn_bytes"]},
+            "cpu_baseline": d.get("cpu_baseline"),
+        })
+    else:
+        line.update({"value": None, "ms_per_step": None})
+    line["workloads"] = res
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -190,6 +190,21 @@ AG_API ag_status ag_debug_validate(const ag_kv_cache* cache, const int32_t* bloc
                             const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* cu_new,
                             int32_t batch, void* stream);
 
+/*
+ * Measurement aid, not part of the serving path.  While enabled on the calling
+ * host thread, every launch of the main kernel of an attention call (the
+ * split kernel of ag_attn_decode, the tile kernel of ag_attn_prefill /
+ * ag_attn_resume, or the general kernel) is bracketed by a pair of HIP events
+ * recorded on the launch stream, up to max_launches pairs.  ag_prof_collect
+ * waits for the recorded events, returns the mean / min / max duration of
+ * those launches in microseconds (any out-pointer may be NULL) and starts a
+ * new series.  ag_prof_disable releases the events.  Host objects only; no
+ * device memory is allocated.
+ */
+AG_API ag_status ag_prof_enable(int32_t max_launches);
+AG_API ag_status ag_prof_collect(double* mean_us, double* min_us, double* max_us, int32_t* n_launches);
+AG_API ag_status ag_prof_disable(void);
+
 AG_API const char* ag_status_string(ag_status s);
 AG_API const char* ag_last_error(void);       /* thread-local; valid until the next failing call on this thread */
 AG_API const char* ag_version(void);

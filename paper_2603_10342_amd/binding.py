@@ -22,7 +22,8 @@ AG_F32, AG_BF16 = 0, 1
 EXPORTS = [
     "ag_kv_append", "ag_attn_prefill", "ag_attn_resume", "ag_attn_decode_workspace_bytes", "ag_attn_decode",
     "ag_stream_create_cumask", "ag_stream_destroy", "ag_cumask_build", "ag_probe_placement", "ag_device_info",
-    "ag_debug_validate", "ag_status_string", "ag_last_error", "ag_version",
+    "ag_debug_validate", "ag_prof_enable", "ag_prof_collect", "ag_prof_disable", "ag_status_string",
+    "ag_last_error", "ag_version",
 ]
 
 
@@ -64,6 +65,9 @@ def lib():
     l.ag_probe_placement.argtypes = [vp, i32, i32, vp]
     l.ag_device_info.argtypes = [C.POINTER(i32), C.POINTER(i32), C.POINTER(i32), C.c_char_p, i32]
     l.ag_debug_validate.argtypes = [cp, i32p, i32, i32p, i32p, i32p, i32, vp]
+    l.ag_prof_enable.argtypes = [i32]
+    l.ag_prof_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i32)]
+    l.ag_prof_disable.argtypes = []
     for name in EXPORTS:
         if name not in ("ag_attn_decode_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
             getattr(l, name).restype = C.c_int
@@ -198,6 +202,20 @@ def ag_debug_validate(cache: KVCache, block_tables, prefix_lens, new_lens, cu_ne
     c = cache.c_struct()
     _check(lib().ag_debug_validate(C.byref(c), _i32(block_tables), block_tables.shape[1], _i32(prefix_lens),
                                    _i32(new_lens), _i32(cu_new), new_lens.shape[0], _stream(stream)))
+
+
+def ag_prof_enable(max_launches: int):
+    _check(lib().ag_prof_enable(max_launches))
+
+
+def ag_prof_collect() -> dict:
+    mean, lo, hi, n = C.c_double(), C.c_double(), C.c_double(), C.c_int32()
+    _check(lib().ag_prof_collect(C.byref(mean), C.byref(lo), C.byref(hi), C.byref(n)))
+    return {"mean_us": mean.value, "min_us": lo.value, "max_us": hi.value, "n": n.value}
+
+
+def ag_prof_disable():
+    _check(lib().ag_prof_disable())
 
 
 def ag_version() -> str:

@@ -27,6 +27,29 @@ ag_status hip_check(hipError_t e, const char* what)
     return AG_ERR_HIP;
 }
 
+struct Prof {
+    bool on = false;
+    int cap = 0, n = 0;
+    bool open = false;
+    std::vector<hipEvent_t> ev;      // 2 per launch: start, stop
+};
+static thread_local Prof g_prof;
+
+void prof_before(hipStream_t st)
+{
+    Prof& p = g_prof;
+    if (!p.on || p.n >= p.cap) return;
+    p.open = hipEventRecord(p.ev[2 * p.n], st) == hipSuccess;
+}
+
+void prof_after(hipStream_t st)
+{
+    Prof& p = g_prof;
+    if (!p.on || !p.open) return;
+    p.open = false;
+    if (hipEventRecord(p.ev[2 * p.n + 1], st) == hipSuccess) ++p.n;
+}
+
 static int log2_exact(int x)
 {
     if (x <= 0 || (x & (x - 1))) return -1;
@@ -300,6 +323,50 @@ ag_status ag_debug_validate(const ag_kv_cache* cache, const int32_t* block_table
         }
     }
     if (cu_new && cu[batch] != run) { set_error("cu_new[batch]=%d, expected %lld", cu[batch], (long long)run); return AG_ERR_INVALID_ARG; }
+    return AG_OK;
+}
+
+ag_status ag_prof_enable(int32_t max_launches)
+{
+    if (max_launches <= 0 || max_launches > (1 << 20)) { set_error("max_launches=%d out of range", max_launches); return AG_ERR_INVALID_ARG; }
+    ag_prof_disable();
+    Prof& p = g_prof;
+    p.ev.resize(2 * (size_t)max_launches);
+    for (size_t i = 0; i < p.ev.size(); ++i) {
+        ag_status st = hip_check(hipEventCreate(&p.ev[i]), "hipEventCreate");
+        if (st) { for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(p.ev[j]); p.ev.clear(); return st; }
+    }
+    p.cap = max_launches; p.n = 0; p.open = false; p.on = true;
+    return AG_OK;
+}
+
+ag_status ag_prof_collect(double* mean_us, double* min_us, double* max_us, int32_t* n_launches)
+{
+    Prof& p = g_prof;
+    if (!p.on) { set_error("profiling is not enabled on this thread"); return AG_ERR_INVALID_ARG; }
+    double sum = 0, lo = 1e30, hi = 0;
+    for (int i = 0; i < p.n; ++i) {
+        ag_status st = hip_check(hipEventSynchronize(p.ev[2 * i + 1]), "hipEventSynchronize");
+        if (st) return st;
+        float ms = 0;
+        if ((st = hip_check(hipEventElapsedTime(&ms, p.ev[2 * i], p.ev[2 * i + 1]), "hipEventElapsedTime"))) return st;
+        const double us = 1e3 * ms;
+        sum += us; lo = us < lo ? us : lo; hi = us > hi ? us : hi;
+    }
+    if (mean_us) *mean_us = p.n ? sum / p.n : 0.0;
+    if (min_us) *min_us = p.n ? lo : 0.0;
+    if (max_us) *max_us = hi;
+    if (n_launches) *n_launches = p.n;
+    p.n = 0; p.open = false;
+    return AG_OK;
+}
+
+ag_status ag_prof_disable(void)
+{
+    Prof& p = g_prof;
+    for (hipEvent_t e : p.ev) (void)hipEventDestroy(e);
+    p.ev.clear();
+    p.on = false; p.cap = 0; p.n = 0; p.open = false;
     return AG_OK;
 }
 

@@ -36,6 +36,10 @@ struct AttnArgs {
 void set_error(const char* fmt, ...);
 ag_status hip_check(hipError_t e, const char* what);
 
+// Event bracket around a main-kernel launch; no-ops unless ag_prof_enable() is active on this thread.
+void prof_before(hipStream_t st);
+void prof_after(hipStream_t st);
+
 // kernel launchers (each returns after enqueueing)
 ag_status launch_kv_append(const CacheView& c, const void* k_new, const void* v_new, const int32_t* bt, int max_pages,
                            const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* cu_new, int batch,

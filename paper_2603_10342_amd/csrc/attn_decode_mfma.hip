@@ -239,7 +239,9 @@ ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     float* ws_ml = ws_o + (size_t)a.batch * a.hq * nsm * D;
     if (a.batch > 65535 || a.c.hkv > 65535) { set_error("batch or KV heads beyond one launch grid"); return AG_ERR_INVALID_ARG; }
     if (a.max_ctx > 0) {
+        prof_before(st);
         hipLaunchKernelGGL(decode_split_kernel, dim3(nsm, a.c.hkv, a.batch), dim3(256), 0, st, a, ws_o, ws_ml, nsm);
+        prof_after(st);
         ag_status e = hip_check(hipGetLastError(), "decode split launch");
         if (e) return e;
     }

@@ -122,10 +122,12 @@ ag_status launch_attn_general(const AttnArgs& a, hipStream_t st)
     const int64_t items = (int64_t)a.total_rows * a.hq;
     const int64_t blocks = (items + 3) / 4;
     if (blocks > 0x7fffffff) { set_error("too many rows for one launch"); return AG_ERR_INVALID_ARG; }
+    prof_before(st);
     if (a.c.dtype == AG_BF16)
         hipLaunchKernelGGL(attn_general_kernel<__bf16>, dim3((unsigned)blocks), dim3(256), 0, st, a);
     else
         hipLaunchKernelGGL(attn_general_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, st, a);
+    prof_after(st);
     return hip_check(hipGetLastError(), "attn_general launch");
 }
 

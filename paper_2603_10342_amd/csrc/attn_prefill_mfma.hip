@@ -297,8 +297,10 @@ ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
     const int64_t total = (int64_t)a.batch * a.hq * q_tiles;
     const int64_t per_xcd = (total + 7) / 8;
     if (per_xcd * 8 > 0x7fffffff) { set_error("too many query tiles for one launch"); return AG_ERR_INVALID_ARG; }
+    prof_before(st);
     hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), kLdsBytes, st, a, q_tiles,
                        (int)per_xcd, total);
+    prof_after(st);
     return hip_check(hipGetLastError(), "prefill launch");
 }
 
