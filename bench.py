@@ -355,6 +355,19 @@ def bench_mixed(args, torch, B, I, info):
     return out
 
 
+def bench_copycal(args, torch):
+    """A plain device-to-device copy of known size: the yardstick the FETCH_SIZE / WRITE_SIZE counters of the
+    attention kernels are scaled by (run this workload under `rocprofv3 --pmc`)."""
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    sec = time_steps(torch, lambda i: dst.copy_(src), 10, 2)
+    out = {"bytes_read": n, "bytes_written": n, "ms": sec * 1e3, "GBps_read_plus_write": 2 * n / sec / 1e9}
+    log("copycal", json.dumps(out))
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -388,6 +401,8 @@ def main():
         res["resume_prefill"] = bench_prefill("resume", args, torch, B, I)
     if "mixed" in want:
         res["mixed"] = bench_mixed(args, torch, B, I, info)
+    if "copycal" in want:
+        res["copycal"] = bench_copycal(args, torch)
 
     d = res.get("decode")
     line = {

@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libagattn.so")
+# AGATTN_LIB selects another build of the same library (kernel tuning experiments); default is the in-tree build.
+LIB_PATH = os.environ.get("AGATTN_LIB") or os.path.join(HERE, "libagattn.so")
 
 AG_OK, AG_ERR_INVALID_ARG, AG_ERR_UNSUPPORTED, AG_ERR_WORKSPACE, AG_ERR_HIP = 0, -1, -2, -3, -4
 AG_F32, AG_BF16 = 0, 1
@@ -117,7 +118,7 @@ class KVCache:
                  device="cuda", fill: Optional[float] = None):
         td = torch_dtype(dtype)
         mk = torch.empty if fill is None else (lambda *a, **k: torch.full(*a, fill_value=fill, **k))
-        self.k_pool = mk((num_pages, num_kv_heads, page_size, head_dim), dtype=td, device=device)
+        self.k_pool = mk((num_pages, num_kv_heads, head_dim // 8, page_size, 8), dtype=td, device=device)
         self.v_pool = mk((num_pages, num_kv_heads, head_dim, page_size), dtype=td, device=device)
         self.num_pages, self.page_size = num_pages, page_size
         self.num_kv_heads, self.head_dim, self.dtype = num_kv_heads, head_dim, dtype
@@ -126,9 +127,18 @@ class KVCache:
         return ag_kv_cache(self.k_pool.data_ptr(), self.v_pool.data_ptr(), self.num_pages, self.page_size,
                            self.num_kv_heads, self.head_dim, self.dtype)
 
+    def k_pool_token_major(self) -> torch.Tensor:
+        """The key pool as [page][head][slot][d] (the library stores [d/8][slot][8])."""
+        return self.k_pool.permute(0, 1, 3, 2, 4).reshape(self.num_pages, self.num_kv_heads, self.page_size,
+                                                           self.head_dim)
+
     def v_pool_token_major(self) -> torch.Tensor:
-        """The value pool viewed as [page][head][slot][d] (a transpose of the stored [d][slot])."""
-        return self.v_pool.transpose(2, 3)
+        """The value pool as [page][head][slot][d] (the library stores [d][column], slot s in column
+        (s & ~12) | ((s & 8) >> 1) | ((s & 4) << 1) for page sizes of 16 and more)."""
+        ps = self.page_size
+        s = torch.arange(ps, device=self.v_pool.device)
+        col = s if ps < 16 else (s & ~12) | ((s & 8) >> 1) | ((s & 4) << 1)
+        return self.v_pool.index_select(3, col).transpose(2, 3)
 
 
 def ag_kv_append(cache: KVCache, k_new, v_new, block_tables, prefix_lens, new_lens, cu_new, total_new: int,

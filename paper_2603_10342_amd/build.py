@@ -18,31 +18,36 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-strict-ali
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 
-def _compile(src: str, extra) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
-    if r.returncode:
-        raise RuntimeError(f"hipcc failed on {src}:\n{err}")
-    if err.strip():
-        sys.stderr.write(err + "\n")
-    return obj
+def build(extra=(), verbose: bool = False, lib: str = LIB, tag: str = "") -> str:
+    """Compile every source and link `lib`.  `extra` are added hipcc flags (e.g. -DAG_DECODE_SPLIT=256);
+    `tag` keeps the objects of a variant build apart."""
+    global OBJ
+    obj_dir = OBJ + tag
+    os.makedirs(obj_dir, exist_ok=True)
 
+    def comp(src):
+        obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+        cmd = [HIPCC] + FLAGS + list(extra) + ["-c", os.path.join(CSRC, src), "-o", obj]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        if r.returncode:
+            raise RuntimeError(f"hipcc failed on {src}:\n{err}")
+        if err.strip():
+            sys.stderr.write(err + "\n")
+        return obj
 
-def build(extra=(), verbose: bool = False) -> str:
-    os.makedirs(OBJ, exist_ok=True)
     with ThreadPoolExecutor(len(SOURCES)) as ex:
-        objs = list(ex.map(lambda s: _compile(s, extra), SOURCES))
-    tmp = LIB + f".tmp{os.getpid()}"
+        objs = list(ex.map(comp, SOURCES))
+    LIBP = lib
+    tmp = LIBP + f".tmp{os.getpid()}"
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode:
         raise RuntimeError("link failed:\n" + r.stderr)
-    os.replace(tmp, LIB)
+    os.replace(tmp, LIBP)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", LIBP)
+    return LIBP
 
 
 if __name__ == "__main__":

@@ -9,10 +9,13 @@
 
 namespace ag {
 
+// Column of slot s inside a value-page row: the two middle quads of every aligned 16 are swapped.
+__host__ __device__ inline int v_col(int slot, int ps) { return ps < 16 ? slot : ((slot & ~12) | ((slot & 8) >> 1) | ((slot & 4) << 1)); }
+
 // Host-validated view of an ag_kv_cache.
 struct CacheView {
-    void* k;          // [num_pages][hkv][ps][d]
-    void* v;          // [num_pages][hkv][d][ps]
+    void* k;          // [num_pages][hkv][d/8][ps][8]
+    void* v;          // [num_pages][hkv][d][ps], columns permuted by v_col
     int num_pages, ps, ps_shift, hkv, d, dtype;
 };
 
@@ -56,6 +59,9 @@ ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st);
 ag_status launch_probe(uint32_t* ids_out, int n_wg, int spin_cycles, hipStream_t st);
 
 // Tokens of context handled by one decode workgroup (one split).
-constexpr int kDecodeSplit = 512;
+#ifndef AG_DECODE_SPLIT
+#define AG_DECODE_SPLIT 512
+#endif
+constexpr int kDecodeSplit = AG_DECODE_SPLIT;
 
 }  // namespace ag

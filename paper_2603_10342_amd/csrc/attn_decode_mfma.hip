@@ -37,24 +37,32 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int PS = 16;
-constexpr int kWaveTok = kDecodeSplit / 4;   // 128 tokens per wave
+constexpr int kWaveTok = kDecodeSplit / 4;   // tokens per wave
 constexpr int kSteps = kWaveTok / 32;        // two pages per step
+static_assert(kSteps >= 1 && kSteps <= 8, "a wave walks 1..8 steps of 32 tokens");
+#ifndef AG_DECODE_PREFETCH
+#define AG_DECODE_PREFETCH 1
+#endif
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ bf16x8 ld16(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
 
-// zero the elements e of a packed bf16x8 whose index is >= keep (0 <= keep < 8 on entry means partial)
-__device__ __forceinline__ bf16x8 keep_first(bf16x8 v, int keep)
+// v holds 8 tokens: elements 0..3 are tokens j = 0..3, elements 4..7 tokens j = 8..11 of the lane's run.
+// Zero element e < 4 unless e < keep_lo, and element 4 + e unless e < keep_hi.
+__device__ __forceinline__ bf16x8 keep_quads(bf16x8 v, int keep_lo, int keep_hi)
 {
     u32x4 u = __builtin_bit_cast(u32x4, v);
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        const uint32_t lo = (2 * w < keep) ? 0x0000FFFFu : 0u;
-        const uint32_t hi = (2 * w + 1 < keep) ? 0xFFFF0000u : 0u;
-        u[w] &= (lo | hi);
+    for (int w = 0; w < 2; ++w) {
+        u[w] &= ((2 * w < keep_lo) ? 0x0000FFFFu : 0u) | ((2 * w + 1 < keep_lo) ? 0xFFFF0000u : 0u);
+        u[2 + w] &= ((2 * w < keep_hi) ? 0x0000FFFFu : 0u) | ((2 * w + 1 < keep_hi) ? 0xFFFF0000u : 0u);
     }
     return __builtin_bit_cast(bf16x8, u);
 }
+
+struct StepRegs {       // one wave's K and V operands for 32 tokens (two pages)
+    bf16x8 k1[4], k2[4], v[8];
+};
 
 __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float* __restrict__ ws_o,
                                                               float* __restrict__ ws_ml, int n_splits_max)
@@ -89,13 +97,14 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
         }
     }
 
-    // physical pages of this wave's 8 logical pages (clamped to the session's last page)
+    // physical pages of this wave's logical pages (clamped to the session's last page)
     const int n_pages_ctx = (ctx + PS - 1) >> 4;
     int my_pid;
     {
-        const int lp = min((wstart >> 4) + (lane & 7), n_pages_ctx - 1);
+        const int lp = min((wstart >> 4) + (lane & (2 * kSteps - 1)), n_pages_ctx - 1);
         my_pid = a.bt[(int64_t)s * a.max_pages + lp];
     }
+    const int n_steps = wstart < ctx ? min(kSteps, (ctx - wstart + 31) >> 5) : 0;   // uniform over the wave
 
     const float sl2 = a.scale * kLog2e;
     float m = -INFINITY, lsum = 0.0f;
@@ -103,46 +112,47 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
 #pragma unroll
     for (int mb = 0; mb < 8; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // row r of the first product: page (r >> 3), slot ((r >> 2) & 1) * 8 + (r & 3); second product: slot + 4
+    // Row r of the first score product is slot (r & 7) of page (r >> 3) of the step; the second product takes
+    // slots 8..15.  K page layout [chunk][slot][8]: lanes r = 0..7 of one lane group read 128 contiguous bytes.
+    // Lane group c then owns slots (c&1)*4 + {0..3} and 8 + (c&1)*4 + {0..3} of page (c >> 1): exactly the 8
+    // columns at offset (c&1)*8 of a value-page row (see v_col), so its 16-byte V load is its P operand's partner.
     const int k_pg = r >> 3;
-    const int k_slot = ((r >> 2) & 1) * 8 + (r & 3);
+    const int k_off = (c * PS + (r & 7)) * 8;            // + kk * 4 * PS * 8 per k-step; + 8 * 8 for slots 8..15
     const int v_pg = c >> 1;
-    const int v_slot = (c & 1) * 8;
+    const int v_off = r * PS + (c & 1) * 8;              // + mb * 16 * PS per channel block
 
-#pragma unroll 1
-    for (int st = 0; st < kSteps; ++st) {
-        const int tok0 = wstart + st * 32;
-        if (tok0 >= ctx) break;          // uniform over the wave
+    auto load_step = [&](int st, StepRegs& x) {
         const int64_t pA = __builtin_amdgcn_readlane(my_pid, 2 * st);
         const int64_t pB = __builtin_amdgcn_readlane(my_pid, 2 * st + 1);
-
-        const __bf16* kp = kpool + ((((k_pg ? pB : pA) * hkv + g) * PS + k_slot) * D) + c * 8;
-        const __bf16* vp = vpool + ((((v_pg ? pB : pA) * hkv + g) * D + r) * PS) + v_slot;
-        bf16x8 k1[4], k2[4], v[8];
+        const __bf16* kp = kpool + ((k_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + k_off;
+        const __bf16* vp = vpool + ((v_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + v_off;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            k1[kk] = ld16(kp + kk * 32);
-            k2[kk] = ld16(kp + 4 * D + kk * 32);
+            x.k1[kk] = ld16(kp + kk * 4 * PS * 8);
+            x.k2[kk] = ld16(kp + kk * 4 * PS * 8 + 64);
         }
 #pragma unroll
-        for (int mb = 0; mb < 8; ++mb) v[mb] = ld16(vp + mb * 16 * PS);
+        for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16(vp + mb * 16 * PS);
+    };
 
+    auto compute_step = [&](int st, StepRegs& x) {
+        const int tok0 = wstart + st * 32;
         f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[kk], qf[kk], s1, 0, 0, 0);
-            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2[kk], qf[kk], s2, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qf[kk], s1, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qf[kk], s2, 0, 0, 0);
         }
-        // this lane's 8 scores are tokens tokb .. tokb + 7 of head r (s1: +0..3, s2: +4..7)
-        const int tokb = tok0 + c * 8;
-        const int keep = ctx - tokb;     // tokens tokb + e with e < keep exist
-        float x[8];
+        // s1[i]: token tokb + i, s2[i]: token tokb + 8 + i, of head r
+        const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
+        const int keep = ctx - tokb;     // token tokb + j exists iff j < keep
+        float xs[8];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            x[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
-            x[4 + i] = (4 + i < keep) ? s2[i] * sl2 : -INFINITY;
+            xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
+            xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
         }
-        float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
+        float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
         mx = fmaxf(mx, __shfl_xor(mx, 16));
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         const float m_new = fmaxf(m, mx);          // finite: token tok0 exists
@@ -151,23 +161,43 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
         bf16x8 pb;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const float p = __builtin_amdgcn_exp2f(x[e] - m_new);
+            const float p = __builtin_amdgcn_exp2f(xs[e] - m_new);
             psum += p;
             pb[e] = (__bf16)p;
         }
         lsum = lsum * alpha + psum;
         m = m_new;
         if (tok0 + 32 > ctx) {           // last, partial step: unwritten slots may hold anything, NaN included
-            const int kp8 = keep < 0 ? 0 : keep;
 #pragma unroll
-            for (int mb = 0; mb < 8; ++mb) v[mb] = keep_first(v[mb], kp8);
+            for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep, keep - 8);
         }
 #pragma unroll
         for (int mb = 0; mb < 8; ++mb) {
             o[mb] *= alpha;
-            o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[mb], pb, o[mb], 0, 0, 0);
+            o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[mb], 0, 0, 0);
+        }
+    };
+
+#if AG_DECODE_PREFETCH
+    StepRegs buf[2];
+    if (n_steps > 0) load_step(0, buf[0]);
+#pragma unroll
+    for (int st = 0; st < kSteps; ++st) {
+        if (st < n_steps) {
+            if (st + 1 < kSteps && st + 1 < n_steps) load_step(st + 1, buf[(st + 1) & 1]);
+            compute_step(st, buf[st & 1]);
         }
     }
+#else
+#pragma unroll
+    for (int st = 0; st < kSteps; ++st) {
+        if (st < n_steps) {
+            StepRegs x;
+            load_step(st, x);
+            compute_step(st, x);
+        }
+    }
+#endif
     lsum += __shfl_xor(lsum, 16);
     lsum += __shfl_xor(lsum, 32);
 

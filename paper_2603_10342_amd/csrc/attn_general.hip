@@ -82,9 +82,9 @@ __global__ __launch_bounds__(256) void attn_general_kernel(AttnArgs a)
         if (valid) {
             page = bt[j >> a.c.ps_shift];
             slot = j & (ps - 1);
-            const T* kr = kp + ((page * hkv + g) * ps + slot) * D;
+            const T* kr = kp + (page * hkv + g) * (int64_t)D * ps + slot * 8;   // chunk c of this slot: + c * ps * 8
             float dot = 0.0f;
-            for (int d = 0; d < D; ++d) dot = fmaf(s_q[w][d], to_f32(kr[d]), dot);
+            for (int d = 0; d < D; ++d) dot = fmaf(s_q[w][d], to_f32(kr[(int64_t)(d >> 3) * ps * 8 + (d & 7)]), dot);
             x = a.scale * dot;
         }
         const float m_new = fmaxf(m, wave_max(x));      // finite: lane 0 of every block is valid
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void attn_general_kernel(AttnArgs a)
             const float pj = __shfl(p, jj);
             const int64_t pg = __shfl((int)page, jj);
             const int sl = __shfl(slot, jj);
-            const T* vr = vp + (pg * hkv + g) * (int64_t)D * ps + sl;
+            const T* vr = vp + (pg * hkv + g) * (int64_t)D * ps + v_col(sl, ps);
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int d = lane + 64 * c;

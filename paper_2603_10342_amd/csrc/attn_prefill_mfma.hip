@@ -49,13 +49,14 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ u32x4 ld16g(const __bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
 
-__device__ __forceinline__ u32x4 keep_first(u32x4 u, int keep)
+// Elements 0..3 of u are slots j0 + {0..3}, elements 4..7 slots j0 + 8 + {0..3}: zero element e < 4 unless
+// e < keep_lo and element 4 + e unless e < keep_hi.
+__device__ __forceinline__ u32x4 keep_quads(u32x4 u, int keep_lo, int keep_hi)
 {
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-        const uint32_t lo = (2 * w < keep) ? 0x0000FFFFu : 0u;
-        const uint32_t hi = (2 * w + 1 < keep) ? 0xFFFF0000u : 0u;
-        u[w] &= (lo | hi);
+    for (int w = 0; w < 2; ++w) {
+        u[w] &= ((2 * w < keep_lo) ? 0x0000FFFFu : 0u) | ((2 * w + 1 < keep_lo) ? 0xFFFF0000u : 0u);
+        u[2 + w] &= ((2 * w < keep_hi) ? 0x0000FFFFu : 0u) | ((2 * w + 1 < keep_hi) ? 0xFFFF0000u : 0u);
     }
     return u;
 }
@@ -113,29 +114,29 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
     }
 
     // ---- copy roles ----
-    const int kc = tid & 15, kslot = tid >> 4;      // K: chunk of 8 channels, slot; pages 0..3 of the tile
+    const int kslot = tid & 15, kc = tid >> 4;      // K: slot, chunk of 8 channels; pages 0..3 of the tile
     const int vd = tid & 127, vpg0 = tid >> 7;      // V: channel row, pages vpg0 and vpg0 + 2
 
     auto load_tile = [&](int t, Stage& st) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int64_t page = bt[min(t * 4 + i, last_page)];
-            st.k[i] = ld16g(kpool + ((page * hkv + g) * PS + kslot) * D + kc * 8);
+            st.k[i] = ld16g(kpool + (page * hkv + g) * (int64_t)(D * PS) + (kc * PS + kslot) * 8);
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int j = vpg0 + 2 * i;
             const int64_t page = bt[min(t * 4 + j, last_page)];
             const __bf16* vp = vpool + ((page * hkv + g) * D + vd) * PS;
+            // a value-page row holds slots 0-3, 8-11 in its first 16 bytes and 4-7, 12-15 in the second
             u32x4 lo = ld16g(vp), hi8 = ld16g(vp + 8);
             const int keep = ctx - (t * BN + j * PS);           // slots < keep hold real tokens
             if (keep < PS) {                                    // unwritten slots may hold anything
-                lo = keep_first(lo, keep);
-                hi8 = keep_first(hi8, keep - 8);
+                lo = keep_quads(lo, keep, keep - 8);
+                hi8 = keep_quads(hi8, keep - 4, keep - 12);
             }
-            // chunk (j, 0) = slots 0-3, 8-11; chunk (j, 1) = slots 4-7, 12-15
-            st.v[2 * i] = u32x4{lo[0], lo[1], hi8[0], hi8[1]};
-            st.v[2 * i + 1] = u32x4{lo[2], lo[3], hi8[2], hi8[3]};
+            st.v[2 * i] = lo;
+            st.v[2 * i + 1] = hi8;
         }
     };
     auto store_tile = [&](int buf, const Stage& st) {

@@ -4,10 +4,10 @@
 //
 // Append is an index map plus a bit-exact copy: new token i of session s goes
 // to logical position P_s + i -> page bt[s][pos / ps], slot pos % ps.
-//   K page  [slot][D]   : a token's row is contiguous, copied as 16/32-byte chunks
-//   V page  [D][slot]   : stored transposed; 16 neighbouring lanes hold 16
-//                         consecutive tokens of one chunk of D, so each store
-//                         instruction writes runs of consecutive slots.
+//   K page  [D/8][slot][8] : chunk-major; a token's row is cut into 8-channel chunks
+//   V page  [D][slot']     : transposed, slots in the order v_col() gives
+// 16 neighbouring lanes hold 16 consecutive tokens of one chunk of D, so each
+// store instruction writes runs of neighbouring slots.
 // One workgroup of 256 threads takes 16 consecutive rows of the token-major
 // input and one KV head.  HBM-bound: 2 * T * 2*Hkv*D*sizeof bytes (read + write).
 #include "ag_internal.h"
@@ -61,29 +61,20 @@ __global__ __launch_bounds__(256) void kv_append_kernel(E* __restrict__ k_pool, 
     const int chunks = d >> 3;   // 8-element chunks per row
     using C8 = Chunk8<E>;
 
-    // K: thread (token = tid / 16, chunk = tid % 16 + 16*r): rows are copied contiguously
-    {
-        const int tok = tid >> 4;
-        const int64_t page = s_page[tok];
-        if (page >= 0) {
-            const E* src = k_new + ((int64_t)(t0 + tok) * hkv + h) * d;
-            E* dst = k_pool + (((int64_t)page * hkv + h) * ps + s_slot[tok]) * d;
-            for (int c = tid & 15; c < chunks; c += 16)
-                *reinterpret_cast<C8*>(dst + c * 8) = *reinterpret_cast<const C8*>(src + c * 8);
-        }
-    }
-    // V: thread (token = tid % 16, chunk = tid / 16 + 16*r): 16 lanes write 16 neighbouring slots
-    {
-        const int tok = tid & 15;
-        const int64_t page = s_page[tok];
-        if (page >= 0) {
-            const E* src = v_new + ((int64_t)(t0 + tok) * hkv + h) * d;
-            E* dst = v_pool + ((int64_t)page * hkv + h) * d * ps + s_slot[tok];
-            for (int c = tid >> 4; c < chunks; c += 16) {
-                const C8 x = *reinterpret_cast<const C8*>(src + c * 8);
+    // thread (token = tid % 16, chunk = tid / 16 + 16*r): 16 neighbouring lanes hold 16 consecutive
+    // tokens of one chunk, so both stores below write runs of neighbouring slots
+    const int tok = tid & 15;
+    const int64_t page = s_page[tok];
+    if (page >= 0) {
+        const int slot = s_slot[tok];
+        const int64_t row = (int64_t)(t0 + tok) * hkv + h;
+        E* kdst = k_pool + ((int64_t)page * hkv + h) * d * ps + (int64_t)slot * 8;        // + chunk * ps * 8
+        E* vdst = v_pool + ((int64_t)page * hkv + h) * d * ps + v_col(slot, ps);          // + channel * ps
+        for (int c = tid >> 4; c < chunks; c += 16) {
+            *reinterpret_cast<C8*>(kdst + (int64_t)c * ps * 8) = *reinterpret_cast<const C8*>(k_new + row * d + c * 8);
+            const C8 x = *reinterpret_cast<const C8*>(v_new + row * d + c * 8);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) dst[(int64_t)(c * 8 + e) * ps] = x.e[e];
-            }
+            for (int e = 0; e < 8; ++e) vdst[(int64_t)(c * 8 + e) * ps] = x.e[e];
         }
     }
 }

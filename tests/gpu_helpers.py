@@ -93,7 +93,7 @@ def gpu_decode(cache, q: torch.Tensor, bt: torch.Tensor, ctx: torch.Tensor, max_
 def pools_match(cache, kp: np.ndarray, vp: np.ndarray, dtype: int):
     """Bit-exact comparison of the device pools with the oracle's host pools (V viewed token-major)."""
     raw = np.uint32 if dtype == I.F32 else np.uint16
-    gk = to_host_raw(cache.k_pool, dtype)
+    gk = to_host_raw(cache.k_pool_token_major().contiguous(), dtype)
     gv = to_host_raw(cache.v_pool_token_major().contiguous(), dtype)
     np.testing.assert_array_equal(gk.view(raw), kp.view(raw))
     np.testing.assert_array_equal(gv.view(raw), vp.view(raw))
