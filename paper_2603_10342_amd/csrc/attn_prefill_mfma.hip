@@ -43,8 +43,16 @@ constexpr int D = 128;
 constexpr int PS = 16;
 constexpr int BM = 128;                 // query rows per workgroup
 constexpr int BN = 64;                  // keys per tile
-constexpr int kTileBytes = BN * D * 2;  // 16 KiB, for K and for V^T alike
-constexpr int kLdsBytes = 4 * kTileBytes;
+// LDS tiles with padded rows: a K row (one key, 256 B) is 272 B apart and a V^T row (one channel, 128 B) 144 B
+// apart, so that the 16-byte operand reads of 16 neighbouring lanes fall in 16 different bank groups while
+// every operand address is the lane's base plus a compile-time offset.
+constexpr int kKRow = 272;
+constexpr int kVRow = 144;
+constexpr int kKTile = BN * kKRow;      // 17408
+constexpr int kVTile = D * kVRow;       // 18432
+constexpr int kStage = kKTile + kVTile; // 35840
+constexpr int kLdsBytes = 2 * kStage;   // 71680: two workgroups per CU fit in 160 KiB
+constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may grow before O is rescaled
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ u32x4 ld16g(const __bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
@@ -75,12 +83,14 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
     const int64_t wk = (int64_t)xcd * per_xcd + ord;
     if (wk >= total_work) return;
     const int hkv = a.c.hkv, hq = a.hq, G = hq / hkv;
-    const int inner = a.batch * G;
-    const int g = (int)(wk / ((int64_t)q_tiles * inner));
-    const int rem = (int)(wk % ((int64_t)q_tiles * inner));
-    const int qt = q_tiles - 1 - rem / inner;
-    const int s = (rem % inner) / G;
-    const int h = g * G + (rem % inner) % G;
+    // work order: KV head, then session, then query tile (longest first), then the G heads of the group, so
+    // that the workgroups resident on one XCD at a time read the same session's K/V for one KV head: it stays in L2
+    const int per_sess = q_tiles * G;
+    const int g = (int)(wk / ((int64_t)a.batch * per_sess));
+    const int rem = (int)(wk % ((int64_t)a.batch * per_sess));
+    const int s = rem / per_sess;
+    const int qt = q_tiles - 1 - (rem % per_sess) / G;
+    const int h = g * G + rem % G;
 
     const int N = a.new_lens[s];
     const int q0 = qt * BM;
@@ -140,19 +150,15 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
         }
     };
     auto store_tile = [&](int buf, const Stage& st) {
-        unsigned char* kb = lds + buf * 2 * kTileBytes;
-        unsigned char* vb = kb + kTileBytes;
+        unsigned char* kb = lds + buf * kStage;
+        unsigned char* vb = kb + kKTile;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int key = i * PS + kslot;
-            *reinterpret_cast<u32x4*>(kb + key * 256 + ((kc ^ (key & 15)) << 4)) = st.k[i];
-        }
-        const int sw = (vd >> 1) & 7;
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(kb + (i * PS + kslot) * kKRow + kc * 16) = st.k[i];
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int j = vpg0 + 2 * i;
-            *reinterpret_cast<u32x4*>(vb + vd * 128 + (((j * 2) ^ sw) << 4)) = st.v[2 * i];
-            *reinterpret_cast<u32x4*>(vb + vd * 128 + (((j * 2 + 1) ^ sw) << 4)) = st.v[2 * i + 1];
+            *reinterpret_cast<u32x4*>(vb + vd * kVRow + (j * 2) * 16) = st.v[2 * i];
+            *reinterpret_cast<u32x4*>(vb + vd * kVRow + (j * 2 + 1) * 16) = st.v[2 * i + 1];
         }
     };
 
@@ -177,22 +183,20 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
         if (more) load_tile(t + 1, stg);
 
         if (t < wave_tiles) {
-            const unsigned char* kb = lds + (t & 1) * 2 * kTileBytes;
-            const unsigned char* vb = kb + kTileBytes;
+            const unsigned char* kb = lds + (t & 1) * kStage + n * kKRow + hi * 16;
+            const unsigned char* vb = lds + (t & 1) * kStage + kKTile + n * kVRow + hi * 16;
             f32x16 sc[2];
 #pragma unroll
             for (int b = 0; b < 2; ++b) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sc[b][i] = 0.f;
-                const int key = b * 32 + n;
 #pragma unroll
                 for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kb + key * 256 + (((ks * 2 + hi) ^ (key & 15)) << 4));
+                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kb + b * 32 * kKRow + ks * 32);
                     sc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sc[b], 0, 0, 0);
                 }
             }
-            // sc[b][i] is key t*64 + b*32 + (i/4)*8 + hi*4 + i%4 against query n
-            float mx = -INFINITY;
+            // sc[b][i] is key t*64 + b*32 + (i/4)*8 + hi*4 + i%4 against query n (raw dot products)
             if (t >= first_masked) {
                 const int kbase = t * BN + hi * 4;
 #pragma unroll
@@ -200,42 +204,46 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = kbase + b * 32 + (i >> 2) * 8 + (i & 3);
-                        sc[b][i] = key <= qpos ? sc[b][i] * sl2 : -INFINITY;
+                        sc[b][i] = key <= qpos ? sc[b][i] : -INFINITY;
                     }
-            } else {
-#pragma unroll
-                for (int b = 0; b < 2; ++b)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sc[b][i] *= sl2;
             }
+            float mx = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[0][2]);
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[0][i]), sc[0][i + 1]);
+            mx = fmaxf(fmaxf(mx, sc[0][15]), sc[1][0]);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sc[b][i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx);       // finite from tile 0 on: key 0 is visible to every row
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            for (int i = 1; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[1][i]), sc[1][i + 1]);
+            mx = fmaxf(mx, sc[1][15]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2;       // scale > 0: max and scaling commute
+            // The reference m only has to stay within a few powers of two of the row maximum (any shift
+            // cancels in O / l), so O is rescaled only when some row's maximum outgrew m by more than the
+            // slack; until then weights may reach 2^slack, harmless in fp32 and bf16.
+            if (__builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0) {       // uniform over the wave
+                const float m_new = fmaxf(m, mx);           // finite from tile 0 on: key 0 is visible to every row
+                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+                lsum *= alpha;
+#pragma unroll
+                for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
+                m = m_new;
+            }
             float psum = 0.f;
             bf16x8 pb[4];
 #pragma unroll
             for (int b = 0; b < 2; ++b)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(sc[b][i] - m_new);
+                    const float p = __builtin_amdgcn_exp2f(fmaf(sc[b][i], sl2, -m));
                     psum += p;
                     pb[b * 2 + (i >> 3)][i & 7] = (__bf16)p;
                 }
-            lsum = lsum * alpha + psum;
-            m = m_new;
+            lsum += psum;
 #pragma unroll
             for (int mb = 0; mb < 4; ++mb) {
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
-                const int d = mb * 32 + n;
-                const int sw = (d >> 1) & 7;
-#pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const bf16x8 va = *reinterpret_cast<const bf16x8*>(vb + d * 128 + (((j * 2 + hi) ^ sw) << 4));
+                    const bf16x8 va = *reinterpret_cast<const bf16x8*>(vb + mb * 32 * kVRow + j * 32);
                     o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j], o[mb], 0, 0, 0);
                 }
             }
