@@ -6,25 +6,37 @@
 // A dense contraction, bound by the matrix cores: 4 * D flop per visible
 // (query, key) pair and head.  One workgroup (4 waves) owns 128 consecutive
 // query rows of one (session, query head); each wave owns 32 rows and keeps
-// their Q in registers.  Keys and values are taken 64 at a time (4 pages),
-// staged through LDS (double buffered, one barrier per tile):
+// their Q in registers.  Keys and values are taken 64 at a time (4 pages) and
+// staged through LDS:
 //
 //   S^T[key][query] = K[key][:] . Q[query][:]      2 x 8 MFMA 32x32x16
-//   streaming softmax per query column (running max / sum, exp2)
+//   softmax weights per query column (running reference m, running sum l, exp2)
 //   O^T[d][query]  += V^T[d][key] . P^T[key][query]  4 x 4 MFMA 32x32x16
 //
 // Computing the transposed score tile puts one query in one lane (plus its
 // partner lane + 32), so the row max / sum need a single cross-lane step,
 // and the 8 scores a lane holds for one k-step of the second product are
-// already the B operand: P never leaves registers.  V pages are stored
-// transposed ([d][slot]); the copy into LDS orders the keys of each 16-byte
-// chunk to match that operand.  Both LDS tiles are XOR-swizzled by row so
-// the 16-byte operand reads are conflict free.
+// already its B operand: P never leaves registers.  V pages are stored
+// transposed with the slot order the score tile produces, so a value row
+// copies straight into LDS.  LDS rows are padded so 16-byte operand reads
+// are conflict free and every operand address is base + constant.
 //
-// Tiles wholly above a wave's rows are skipped; only tiles that straddle the
-// diagonal are masked.  Workgroups are numbered so that the XCD a workgroup
-// lands on (id % 8) owns a contiguous range of KV heads, keeping a session's
-// K/V for that head in one L2, and within it the longest query tiles go first.
+// The per-element softmax work on the vector ALUs is about as long as the
+// matrix work (one exp per 512 flop), so the loop is software pipelined to
+// run them side by side inside a wave.  Iteration t of a wave holds three
+// independent pieces
+//        S(t+1) = K(t+1).Q^T   (matrix)      P(t) = exp2(S(t) - m)   (vector)
+//        O     += V(t-1).P(t-1) (matrix)
+// in one basic block.  m is a reference, not the exact running maximum: O is
+// rescaled only when a row's maximum has outgrown m by more than 2^8, which
+// is decided before the block starts and takes a slower, ordered path, as do
+// the tiles that straddle the diagonal (the only ones that need a mask).
+// Tiles wholly above a wave's rows are skipped.
+//
+// Workgroups are numbered so that the XCD a workgroup lands on (id % 8) owns a
+// contiguous range of KV heads, and inside it session-major, longest query
+// tile first: the workgroups resident together read one session's K/V for one
+// KV head, which then stays in that XCD's L2.
 #include <atomic>
 
 #include "ag_internal.h"
@@ -37,7 +49,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 128;
 constexpr int PS = 16;
@@ -50,10 +61,16 @@ constexpr int kKRow = 272;
 constexpr int kVRow = 144;
 constexpr int kKTile = BN * kKRow;      // 17408
 constexpr int kVTile = D * kVRow;       // 18432
-constexpr int kStage = kKTile + kVTile; // 35840
-constexpr int kLdsBytes = 2 * kStage;   // 71680: two workgroups per CU fit in 160 KiB
+constexpr int kLdsBytes = 2 * (kKTile + kVTile);   // two K tiles, then two V tiles: 71680
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may grow before O is rescaled
 constexpr float kLog2e = 1.4426950408889634f;
+
+#ifndef AG_PREFILL_WAVES_PER_SIMD
+#define AG_PREFILL_WAVES_PER_SIMD 2
+#endif
+#ifndef AG_PREFILL_AHEAD
+#define AG_PREFILL_AHEAD 3
+#endif
 
 __device__ __forceinline__ u32x4 ld16g(const __bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
 
@@ -69,12 +86,68 @@ __device__ __forceinline__ u32x4 keep_quads(u32x4 u, int keep_lo, int keep_hi)
     return u;
 }
 
+// S^T tile (64 keys x 32 queries) = K tile . Q^T.  kb: this lane's base in a K tile (row n, half hi).
+__device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&qf)[8], f32x16 (&sc)[2])
+{
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sc[b][i] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+            const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kb + b * 32 * kKRow + ks * 32);
+            sc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sc[b], 0, 0, 0);
+        }
+    }
+}
+
+// O^T (128 channels x 32 queries) += V^T tile . P^T.  vb: this lane's base in a V tile (row n, half hi).
+__device__ __forceinline__ void pv_tile(const unsigned char* vb, const bf16x8 (&pb)[4], f32x16 (&o)[4])
+{
+#pragma unroll
+    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const bf16x8 va = *reinterpret_cast<const bf16x8*>(vb + mb * 32 * kVRow + j * 32);
+            o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j], o[mb], 0, 0, 0);
+        }
+}
+
+// Largest raw score of this lane's query in the tile (both half-lanes combined).
+__device__ __forceinline__ float row_max(const f32x16 (&sc)[2])
+{
+    float mx = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[0][2]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[0][i]), sc[0][i + 1]);
+    mx = fmaxf(fmaxf(mx, sc[0][15]), sc[1][0]);
+#pragma unroll
+    for (int i = 1; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[1][i]), sc[1][i + 1]);
+    mx = fmaxf(mx, sc[1][15]);
+    return fmaxf(mx, __shfl_xor(mx, 32));
+}
+
+// P^T = exp2(S^T * sl2 - m) packed as the B operands of the four k-steps of the second product; adds to lsum.
+__device__ __forceinline__ void exp_tile(const f32x16 (&sc)[2], float sl2, float m, float& lsum, bf16x8 (&pb)[4])
+{
+    float psum = 0.f;
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(sc[b][i], sl2, -m));
+            psum += p;
+            pb[b * 2 + (i >> 3)][i & 7] = (__bf16)p;
+        }
+    lsum += psum;
+}
+
 struct Stage {          // one thread's share of a K tile and a V tile on its way to LDS
     u32x4 k[4];
     u32x4 v[4];
 };
 
-__global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_tiles, int per_xcd, int64_t total_work)
+__global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int q_tiles,
+                                                                                      int per_xcd, int64_t total_work)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
@@ -83,8 +156,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
     const int64_t wk = (int64_t)xcd * per_xcd + ord;
     if (wk >= total_work) return;
     const int hkv = a.c.hkv, hq = a.hq, G = hq / hkv;
-    // work order: KV head, then session, then query tile (longest first), then the G heads of the group, so
-    // that the workgroups resident on one XCD at a time read the same session's K/V for one KV head: it stays in L2
+    // work order: KV head, then session, then query tile (longest first), then the G heads of the group
     const int per_sess = q_tiles * G;
     const int g = (int)(wk / ((int64_t)a.batch * per_sess));
     const int rem = (int)(wk % ((int64_t)a.batch * per_sess));
@@ -105,8 +177,8 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
     const int qrow0 = 32 * w;                       // first row of this wave inside the tile
     const int rows_w = max(0, min(32, rows_wg - qrow0));
 
-    const int n_tiles = (P + q0 + rows_wg - 1) / BN + 1;
-    const int wave_tiles = rows_w > 0 ? (P + q0 + qrow0 + rows_w - 1) / BN + 1 : 0;
+    const int n_tiles = (P + q0 + rows_wg - 1) / BN + 1;                        // tiles the workgroup stages
+    const int wave_tiles = rows_w > 0 ? (P + q0 + qrow0 + rows_w - 1) / BN + 1 : 0;   // tiles this wave uses
     const int first_masked = (P + q0 + qrow0 + 1) / BN;   // first tile holding a key this wave's row 0 may not see
 
     const __bf16* kpool = (const __bf16*)a.c.k;
@@ -125,22 +197,33 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
 
     // ---- copy roles ----
     const int kslot = tid & 15, kc = tid >> 4;      // K: slot, chunk of 8 channels; pages 0..3 of the tile
-    const int vd = tid & 127, vpg0 = tid >> 7;      // V: channel row, pages vpg0 and vpg0 + 2
+    const int vd = tid & 127;                       // V: channel row, pages vpg0 and vpg0 + 2
+    const int vpg0 = __builtin_amdgcn_readfirstlane(tid >> 7);   // uniform over a wave: keeps page ids scalar
+    unsigned char* const k_lds = lds;                // K tile t lives at k_lds + (t & 1) * kKTile
+    unsigned char* const v_lds = lds + 2 * kKTile;   // V tile t lives at v_lds + (t & 1) * kVTile
 
-    auto load_tile = [&](int t, Stage& st) {
+    // Physical pages of a tile, through scalar loads (the index is uniform).  They are fetched one iteration
+    // before the tile's data is requested, so no data load ever waits for a block-table read.
+    struct Pages { int k[4]; int v[2]; };
+    auto pages_of = [&](int tk, int tv, Pages& pg) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int64_t page = bt[min(t * 4 + i, last_page)];
-            st.k[i] = ld16g(kpool + (page * hkv + g) * (int64_t)(D * PS) + (kc * PS + kslot) * 8);
-        }
+        for (int i = 0; i < 4; ++i) pg.k[i] = bt[min(tk * 4 + i, last_page)];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) pg.v[i] = bt[min(tv * 4 + vpg0 + 2 * i, last_page)];
+    };
+    auto load_k = [&](const int (&pid)[4], Stage& st) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            st.k[i] = ld16g(kpool + ((int64_t)pid[i] * hkv + g) * (int64_t)(D * PS) + (kc * PS + kslot) * 8);
+    };
+    auto load_v = [&](int t, const int (&pid)[2], Stage& st) {
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int j = vpg0 + 2 * i;
-            const int64_t page = bt[min(t * 4 + j, last_page)];
-            const __bf16* vp = vpool + ((page * hkv + g) * D + vd) * PS;
+            const __bf16* vp = vpool + (((int64_t)pid[i] * hkv + g) * D + vd) * PS;
             // a value-page row holds slots 0-3, 8-11 in its first 16 bytes and 4-7, 12-15 in the second
             u32x4 lo = ld16g(vp), hi8 = ld16g(vp + 8);
-            const int keep = ctx - (t * BN + j * PS);           // slots < keep hold real tokens
+            const int keep = ctx - (t * BN + j * PS);           // slots < keep hold real tokens (uniform)
             if (keep < PS) {                                    // unwritten slots may hold anything
                 lo = keep_quads(lo, keep, keep - 8);
                 hi8 = keep_quads(hi8, keep - 4, keep - 12);
@@ -149,11 +232,13 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
             st.v[2 * i + 1] = hi8;
         }
     };
-    auto store_tile = [&](int buf, const Stage& st) {
-        unsigned char* kb = lds + buf * kStage;
-        unsigned char* vb = kb + kKTile;
+    auto store_k = [&](int t, const Stage& st) {
+        unsigned char* kb = k_lds + (t & 1) * kKTile;
 #pragma unroll
         for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(kb + (i * PS + kslot) * kKRow + kc * 16) = st.k[i];
+    };
+    auto store_v = [&](int t, const Stage& st) {
+        unsigned char* vb = v_lds + (t & 1) * kVTile;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int j = vpg0 + 2 * i;
@@ -163,6 +248,7 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
     };
 
     const float sl2 = a.scale * kLog2e;
+    const int qpos = P + q0 + qrow0 + n;            // logical position of this lane's query
     float m = -INFINITY, lsum = 0.f;
     f32x16 o[4];
 #pragma unroll
@@ -170,34 +256,37 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
 
+    const unsigned char* const k_lane = k_lds + n * kKRow + hi * 16;
+    const unsigned char* const v_lane = v_lds + n * kVRow + hi * 16;
+
+    // ---- prologue: K(0) into LDS ----
     Stage stg;
-    load_tile(0, stg);
-    store_tile(0, stg);
+    Pages pg;
+    pages_of(0, 0, pg);
+    load_k(pg.k, stg);
+    store_k(0, stg);
+    pages_of(min(1, n_tiles - 1), 0, pg);            // what iteration 0 requests: K(1) and V(0)
     __syncthreads();
+    f32x16 sc[2];
+    bf16x8 pa[4], pb[4];
 
-    const int qpos = P + q0 + qrow0 + n;            // logical position of this lane's query
-
-#pragma unroll 1
-    for (int t = 0; t < n_tiles; ++t) {
-        const bool more = t + 1 < n_tiles;
-        if (more) load_tile(t + 1, stg);
-
-        if (t < wave_tiles) {
-            const unsigned char* kb = lds + (t & 1) * kStage + n * kKRow + hi * 16;
-            const unsigned char* vb = lds + (t & 1) * kStage + kKTile + n * kVRow + hi * 16;
-            f32x16 sc[2];
-#pragma unroll
-            for (int b = 0; b < 2; ++b) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sc[b][i] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < 8; ++ks) {
-                    const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kb + b * 32 * kKRow + ks * 32);
-                    sc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sc[b], 0, 0, 0);
-                }
-            }
-            // sc[b][i] is key t*64 + b*32 + (i/4)*8 + hi*4 + i%4 against query n (raw dot products)
-            if (t >= first_masked) {
+    // Iteration t of a wave: S(t) from K(t) (matrix); then P(t) = exp2(S(t) - m) (vector) side by side with
+    // O += V(t-1).P(t-1) (matrix).  Global loads for K(t+1) and V(t) are issued at its start and land in LDS
+    // at its end.  Every wave runs all n_tiles + 1 iterations (the barriers are workgroup-wide); the pieces a
+    // wave does not need are skipped.
+    auto iter = [&](int t, bf16x8 (&p_prev)[4], bf16x8 (&p_cur)[4]) {
+        // Requests are unconditional (past the last tile they repeat it into a buffer nobody reads): the
+        // loop body has one shape, so no wait is ever placed ahead of the compute on behalf of a skipped store.
+        load_k(pg.k, stg);
+        load_v(min(t, n_tiles - 1), pg.v, stg);
+        pages_of(min(t + 2, n_tiles - 1), min(t + 1, n_tiles - 1), pg);   // for the next iteration's requests
+        const bool do_sm = t < wave_tiles, do_pv = t >= 1 && t <= wave_tiles;
+        const unsigned char* kb = k_lane + (t & 1) * kKTile;
+        const unsigned char* vb = v_lane + ((t + 1) & 1) * kVTile;
+        float mx = -INFINITY;
+        if (do_sm) {
+            qk_tile(kb, qf, sc);
+            if (t >= first_masked) {                 // the tile straddles this wave's diagonal
                 const int kbase = t * BN + hi * 4;
 #pragma unroll
                 for (int b = 0; b < 2; ++b)
@@ -207,50 +296,60 @@ __global__ __launch_bounds__(256, 2) void prefill_mfma_kernel(AttnArgs a, int q_
                         sc[b][i] = key <= qpos ? sc[b][i] : -INFINITY;
                     }
             }
-            float mx = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[0][2]);
+            mx = row_max(sc) * sl2;                  // scale > 0: max and scaling commute
+        }
+        const bool grow = __builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0;   // uniform over the wave
+        if (do_sm && do_pv && !grow) {
+            // the common case: two independent pieces, interleaved by hand.  Step i issues the operand read
+            // of matrix instruction i + kAhead, matrix instruction i, and the exp of scores 2i and 2i + 1;
+            // the fences keep the compiler from regrouping them.  Neighbouring matrix instructions belong
+            // to different accumulators.
+            constexpr int kAhead = AG_PREFILL_AHEAD;
+            bf16x8 opnd[kAhead + 1];
+            auto operand = [&](int i) -> const unsigned char* {   // order (j, mb)
+                return vb + (i & 3) * 32 * kVRow + (i >> 2) * 32;
+            };
 #pragma unroll
-            for (int i = 3; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[0][i]), sc[0][i + 1]);
-            mx = fmaxf(fmaxf(mx, sc[0][15]), sc[1][0]);
-#pragma unroll
-            for (int i = 1; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[1][i]), sc[1][i + 1]);
-            mx = fmaxf(mx, sc[1][15]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32)) * sl2;       // scale > 0: max and scaling commute
-            // The reference m only has to stay within a few powers of two of the row maximum (any shift
-            // cancels in O / l), so O is rescaled only when some row's maximum outgrew m by more than the
-            // slack; until then weights may reach 2^slack, harmless in fp32 and bf16.
-            if (__builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0) {       // uniform over the wave
-                const float m_new = fmaxf(m, mx);           // finite from tile 0 on: key 0 is visible to every row
-                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-                lsum *= alpha;
-#pragma unroll
-                for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
-                m = m_new;
-            }
+            for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
             float psum = 0.f;
-            bf16x8 pb[4];
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(sc[b][i], sl2, -m));
-                    psum += p;
-                    pb[b * 2 + (i >> 3)][i & 7] = (__bf16)p;
-                }
+            for (int i = 0; i < 16; ++i) {
+                if (i + kAhead < 16) opnd[(i + kAhead) % (kAhead + 1)] = *reinterpret_cast<const bf16x8*>(operand(i + kAhead));
+                o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], p_prev[i >> 2], o[i & 3], 0, 0, 0);
+                const int e = 2 * i;
+                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][e & 15], sl2, -m));
+                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][(e & 15) + 1], sl2, -m));
+                psum += p0 + p1;
+                p_cur[e >> 3][e & 7] = (__bf16)p0;
+                p_cur[e >> 3][(e & 7) + 1] = (__bf16)p1;
+                __builtin_amdgcn_sched_barrier(0);
+            }
             lsum += psum;
+        } else {
+            if (do_pv) pv_tile(vb, p_prev, o);
+            if (do_sm) {
+                if (grow) {
+                    const float m_new = fmaxf(m, mx);    // finite from tile 0 on: key 0 is visible to every row
+                    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+                    lsum *= alpha;
 #pragma unroll
-            for (int mb = 0; mb < 4; ++mb) {
+                    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const bf16x8 va = *reinterpret_cast<const bf16x8*>(vb + mb * 32 * kVRow + j * 32);
-                    o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j], o[mb], 0, 0, 0);
+                        for (int i = 0; i < 16; ++i) o[mb][i] *= alpha;
+                    m = m_new;
                 }
+                exp_tile(sc, sl2, m, lsum, p_cur);
             }
         }
-
-        if (more) store_tile((t + 1) & 1, stg);
+        store_k(t + 1, stg);
+        store_v(t, stg);
         __syncthreads();
+    };
+
+#pragma unroll 1
+    for (int t = 0; t <= n_tiles; t += 2) {
+        iter(t, pb, pa);
+        if (t + 1 <= n_tiles) iter(t + 1, pa, pb);
     }
 
     // ---- normalise, transpose through LDS, store rows contiguously ----
