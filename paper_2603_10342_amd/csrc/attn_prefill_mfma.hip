@@ -87,17 +87,24 @@ __device__ __forceinline__ u32x4 keep_quads(u32x4 u, int keep_lo, int keep_hi)
 }
 
 // S^T tile (64 keys x 32 queries) = K tile . Q^T.  kb: this lane's base in a K tile (row n, half hi).
+// Operand reads run kAhead matrix instructions ahead of their use; the two key blocks alternate so that
+// neighbouring matrix instructions write different accumulators.
 __device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&qf)[8], f32x16 (&sc)[2])
 {
+    constexpr int kAhead = AG_PREFILL_AHEAD;
+    bf16x8 opnd[kAhead + 1];
+    auto operand = [&](int i) -> const unsigned char* { return kb + (i & 1) * 32 * kKRow + (i >> 1) * 32; };
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) sc[b][i] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-            const bf16x8 ka = *reinterpret_cast<const bf16x8*>(kb + b * 32 * kKRow + ks * 32);
-            sc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qf[ks], sc[b], 0, 0, 0);
-        }
+    for (int i = 0; i < 16; ++i) {
+        if (i + kAhead < 16) opnd[(i + kAhead) % (kAhead + 1)] = *reinterpret_cast<const bf16x8*>(operand(i + kAhead));
+        sc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], qf[i >> 1], sc[i & 1], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
