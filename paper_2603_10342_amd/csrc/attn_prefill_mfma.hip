@@ -120,7 +120,7 @@ __device__ __forceinline__ void pv_tile(const unsigned char* vb, const bf16x8 (&
         }
 }
 
-// Largest raw score of this lane's query in the tile (both half-lanes combined).
+// Largest raw score among the 32 keys this lane holds for its query (its partner lane ^ 32 holds the other 32).
 __device__ __forceinline__ float row_max(const f32x16 (&sc)[2])
 {
     float mx = fmaxf(fmaxf(sc[0][0], sc[0][1]), sc[0][2]);
@@ -130,7 +130,7 @@ __device__ __forceinline__ float row_max(const f32x16 (&sc)[2])
 #pragma unroll
     for (int i = 1; i < 15; i += 2) mx = fmaxf(fmaxf(mx, sc[1][i]), sc[1][i + 1]);
     mx = fmaxf(mx, sc[1][15]);
-    return fmaxf(mx, __shfl_xor(mx, 32));
+    return mx;
 }
 
 // P^T = exp2(S^T * sl2 - m) packed as the B operands of the four k-steps of the second product; adds to lsum.
@@ -305,6 +305,8 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
             }
             mx = row_max(sc) * sl2;                  // scale > 0: max and scaling commute
         }
+        // m is shared by the two lanes of a query, but the test needs no exchange: if either lane's own
+        // maximum outgrew m the whole wave takes the ordered path, which combines the two halves.
         const bool grow = __builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0;   // uniform over the wave
         if (do_sm && do_pv && !grow) {
             // the common case: two independent pieces, interleaved by hand.  Step i issues the operand read
@@ -336,6 +338,7 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
             if (do_pv) pv_tile(vb, p_prev, o);
             if (do_sm) {
                 if (grow) {
+                    mx = fmaxf(mx, __shfl_xor(mx, 32));
                     const float m_new = fmaxf(m, mx);    // finite from tile 0 on: key 0 is visible to every row
                     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
                     lsum *= alpha;
