@@ -54,14 +54,16 @@ constexpr int D = 128;
 constexpr int PS = 16;
 constexpr int BM = 128;                 // query rows per workgroup
 constexpr int BN = 64;                  // keys per tile
-// LDS tiles with padded rows: a K row (one key, 256 B) is 272 B apart and a V^T row (one channel, 128 B) 144 B
-// apart, so that the 16-byte operand reads of 16 neighbouring lanes fall in 16 different bank groups while
-// every operand address is the lane's base plus a compile-time offset.
-constexpr int kKRow = 272;
-constexpr int kVRow = 144;
-constexpr int kKTile = BN * kKRow;      // 17408
-constexpr int kVTile = D * kVRow;       // 18432
-constexpr int kLdsBytes = 2 * (kKTile + kVTile);   // two K tiles, then two V tiles: 71680
+// LDS tiles are chunk-major, like the pages themselves, and are filled by direct global-to-LDS loads:
+//   K tile [chunk c = 0..15][key 0..63][8 ch]   operand of key n, chunk c at (c * 64 + n) * 16 bytes
+//   V tile [chunk q = 0..7 ][ch  0..127][8 keys] operand of channel d, chunk q at (q * 128 + d) * 16 bytes
+// (q = 2 * page + half; the 8 keys of a chunk are slots half*4 + {0..3} and 8 + half*4 + {0..3} of the page).
+// The 32 lanes of a half-wave read 32 consecutive 16-byte pieces: conflict free, and every operand address
+// is the lane's base plus a compile-time offset.
+constexpr int kTile = BN * D * 2;       // 16 KiB, K and V alike
+constexpr int kKStages = 3;             // K(t+2) is requested while K(t) is used
+constexpr int kVStages = 2;             // V(t) is requested while V(t-1) is used
+constexpr int kLdsBytes = (kKStages + kVStages) * kTile;   // 80 KiB: two workgroups per CU
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may grow before O is rescaled
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -86,14 +88,14 @@ __device__ __forceinline__ u32x4 keep_quads(u32x4 u, int keep_lo, int keep_hi)
     return u;
 }
 
-// S^T tile (64 keys x 32 queries) = K tile . Q^T.  kb: this lane's base in a K tile (row n, half hi).
+// S^T tile (64 keys x 32 queries) = K tile . Q^T.  kb: this lane's base in a K tile (key n, chunk hi).
 // Operand reads run kAhead matrix instructions ahead of their use; the two key blocks alternate so that
 // neighbouring matrix instructions write different accumulators.
 __device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&qf)[8], f32x16 (&sc)[2])
 {
     constexpr int kAhead = AG_PREFILL_AHEAD;
     bf16x8 opnd[kAhead + 1];
-    auto operand = [&](int i) -> const unsigned char* { return kb + (i & 1) * 32 * kKRow + (i >> 1) * 32; };
+    auto operand = [&](int i) -> const unsigned char* { return kb + (i & 1) * 512 + (i >> 1) * 2048; };   // (ks, b)
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
 #pragma unroll
@@ -108,16 +110,21 @@ __device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&
     }
 }
 
-// O^T (128 channels x 32 queries) += V^T tile . P^T.  vb: this lane's base in a V tile (row n, half hi).
+// O^T (128 channels x 32 queries) += V^T tile . P^T.  vb: this lane's base in a V tile (channel n, chunk hi).
+// Same operand ring as qk_tile (it also bounds the registers the compiler may spend on early reads).
 __device__ __forceinline__ void pv_tile(const unsigned char* vb, const bf16x8 (&pb)[4], f32x16 (&o)[4])
 {
+    constexpr int kAhead = AG_PREFILL_AHEAD;
+    bf16x8 opnd[kAhead + 1];
+    auto operand = [&](int i) -> const unsigned char* { return vb + (i & 3) * 512 + (i >> 2) * 4096; };   // (j, mb)
 #pragma unroll
-    for (int mb = 0; mb < 4; ++mb)
+    for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const bf16x8 va = *reinterpret_cast<const bf16x8*>(vb + mb * 32 * kVRow + j * 32);
-            o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[j], o[mb], 0, 0, 0);
-        }
+    for (int i = 0; i < 16; ++i) {
+        if (i + kAhead < 16) opnd[(i + kAhead) % (kAhead + 1)] = *reinterpret_cast<const bf16x8*>(operand(i + kAhead));
+        o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], pb[i >> 2], o[i & 3], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    }
 }
 
 // Largest raw score among the 32 keys this lane holds for its query (its partner lane ^ 32 holds the other 32).
@@ -148,10 +155,23 @@ __device__ __forceinline__ void exp_tile(const f32x16 (&sc)[2], float sl2, float
     lsum += psum;
 }
 
-struct Stage {          // one thread's share of a K tile and a V tile on its way to LDS
-    u32x4 k[4];
-    u32x4 v[4];
-};
+// One wave-wide direct global-to-LDS load: lane l's 16 bytes at src land at LDS byte address lds_addr + l * 16
+// (lds_addr is uniform and goes through M0).  Written as one asm statement so that nothing can come between the
+// M0 write and its use (the compiler keeps nothing live in M0 on this target: it writes M0 immediately before each
+// of its own uses), and so that the compiler does not model it: it would otherwise make every later LDS
+// operand read wait for all outstanding tile loads.  Completion is tracked by hand with AG_WAIT_VMCNT; the
+// loop contains no other vector memory instruction, so the counter holds exactly these loads.
+__device__ __forceinline__ void load_to_lds(const void* src, unsigned lds_addr)
+{
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_addr));
+}
+__device__ __forceinline__ unsigned lds_address(const void* p)
+{
+    return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8 left at maximum).
+#define AG_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (0xF << 8))
 
 __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int q_tiles,
                                                                                       int per_xcd, int64_t total_work)
@@ -179,6 +199,8 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
     const int64_t t_base = (int64_t)a.cu_new[s] + q0;
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int wu = __builtin_amdgcn_readfirstlane(w);           // the same value, known to be uniform: used only
+                                                                 // where a scalar is required (page ids, M0)
     const int n = lane & 31, hi = lane >> 5;
     const int rows_wg = min(BM, N - q0);            // valid query rows of this workgroup
     const int qrow0 = 32 * w;                       // first row of this wave inside the tile
@@ -190,7 +212,10 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
 
     const __bf16* kpool = (const __bf16*)a.c.k;
     const __bf16* vpool = (const __bf16*)a.c.v;
-    const int32_t* bt = a.bt + (int64_t)s * a.max_pages;
+    // the block table is read-only for the kernel's lifetime: reading it through the constant address space
+    // lets the (uniform) page-id loads be scalar loads, which use their own counter
+    typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+    const cptr_t bt = (cptr_t)(uintptr_t)(a.bt + (int64_t)s * a.max_pages);
     const int last_page = (ctx - 1) >> 4;
 
     // ---- Q^T as B operand: column n = query row, k-step ks covers channels ks*16 + hi*8 .. +7 ----
@@ -202,55 +227,50 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
         for (int ks = 0; ks < 8; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16);
     }
 
-    // ---- copy roles ----
-    const int kslot = tid & 15, kc = tid >> 4;      // K: slot, chunk of 8 channels; pages 0..3 of the tile
-    const int vd = tid & 127;                       // V: channel row, pages vpg0 and vpg0 + 2
-    const int vpg0 = __builtin_amdgcn_readfirstlane(tid >> 7);   // uniform over a wave: keeps page ids scalar
-    unsigned char* const k_lds = lds;                // K tile t lives at k_lds + (t & 1) * kKTile
-    unsigned char* const v_lds = lds + 2 * kKTile;   // V tile t lives at v_lds + (t & 1) * kVTile
+    // ---- tile requests: direct global-to-LDS loads, 4 + 4 wave-wide instructions per wave and tile ----
+    unsigned char* const k_lds = lds;                       // K tile t lives at k_lds + (t % 3) * kTile
+    unsigned char* const v_lds = lds + kKStages * kTile;    // V tile t lives at v_lds + (t & 1) * kTile
+    const int kpg = lane >> 4, kslot = lane & 15;           // K: lane = key of the tile (page, slot)
 
-    // Physical pages of a tile, through scalar loads (the index is uniform).  They are fetched one iteration
-    // before the tile's data is requested, so no data load ever waits for a block-table read.
-    struct Pages { int k[4]; int v[2]; };
+    // Physical pages of a tile, through scalar loads (the index is uniform), fetched one iteration before the
+    // tile's data is requested, so no data request ever waits for a block-table read.
+    struct Pages { int k[4]; int v; };
     auto pages_of = [&](int tk, int tv, Pages& pg) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) pg.k[i] = bt[min(tk * 4 + i, last_page)];
-#pragma unroll
-        for (int i = 0; i < 2; ++i) pg.v[i] = bt[min(tv * 4 + vpg0 + 2 * i, last_page)];
+        pg.v = bt[min(tv * 4 + wu, last_page)];              // wave w brings in page w of the V tile
     };
-    auto load_k = [&](const int (&pid)[4], Stage& st) {
+    // K(tk): instruction i of wave w moves chunk c = 4w + i of all 64 keys: four 256-byte runs, one per page.
+    auto request_k = [&](int tk, const int (&pid)[4]) {
+        const int mine = kpg == 0 ? pid[0] : kpg == 1 ? pid[1] : kpg == 2 ? pid[2] : pid[3];
+        const unsigned char* src = (const unsigned char*)kpool + ((int64_t)mine * hkv + g) * (int64_t)(D * PS * 2) +
+                                   (wu * 4) * 256 + kslot * 16;
+        const unsigned dst = lds_address(k_lds) + (tk % kKStages) * kTile + (wu * 4) * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            st.k[i] = ld16g(kpool + ((int64_t)pid[i] * hkv + g) * (int64_t)(D * PS) + (kc * PS + kslot) * 8);
+        for (int i = 0; i < 4; ++i) load_to_lds(src + i * 256, dst + i * 1024);
     };
-    auto load_v = [&](int t, const int (&pid)[2], Stage& st) {
+    // V(tv): wave w moves page w: instruction (half, dh) moves the 16-byte half `half` of 64 channel rows.
+    auto request_v = [&](int stage, int pid) {
+        const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 32;
+        const unsigned dst = lds_address(v_lds) + stage * kTile + (2 * wu) * 2048;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = vpg0 + 2 * i;
-            const __bf16* vp = vpool + (((int64_t)pid[i] * hkv + g) * D + vd) * PS;
-            // a value-page row holds slots 0-3, 8-11 in its first 16 bytes and 4-7, 12-15 in the second
-            u32x4 lo = ld16g(vp), hi8 = ld16g(vp + 8);
-            const int keep = ctx - (t * BN + j * PS);           // slots < keep hold real tokens (uniform)
-            if (keep < PS) {                                    // unwritten slots may hold anything
-                lo = keep_quads(lo, keep, keep - 8);
-                hi8 = keep_quads(hi8, keep - 4, keep - 12);
-            }
-            st.v[2 * i] = lo;
-            st.v[2 * i + 1] = hi8;
-        }
+        for (int half = 0; half < 2; ++half)
+#pragma unroll
+            for (int dh = 0; dh < 2; ++dh) load_to_lds(src + dh * 64 * 32 + half * 16, dst + half * 2048 + dh * 1024);
     };
-    auto store_k = [&](int t, const Stage& st) {
-        unsigned char* kb = k_lds + (t & 1) * kKTile;
+    // Slots of the session's last page that hold no token may contain anything (NaN included) and would poison
+    // the value product even under a zero weight: once V(tv) has landed, zero them in LDS.
+    auto scrub_v = [&](int stage, int tv) {
+        const int keep = ctx - (tv * BN + w * PS);              // slots < keep of this wave's page hold tokens
+        if (keep < PS) {                                        // uniform over the wave
+            unsigned char* base = v_lds + stage * kTile + (2 * w) * 2048 + lane * 16;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4*>(kb + (i * PS + kslot) * kKRow + kc * 16) = st.k[i];
-    };
-    auto store_v = [&](int t, const Stage& st) {
-        unsigned char* vb = v_lds + (t & 1) * kVTile;
+            for (int half = 0; half < 2; ++half)
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const int j = vpg0 + 2 * i;
-            *reinterpret_cast<u32x4*>(vb + vd * kVRow + (j * 2) * 16) = st.v[2 * i];
-            *reinterpret_cast<u32x4*>(vb + vd * kVRow + (j * 2 + 1) * 16) = st.v[2 * i + 1];
+                for (int dh = 0; dh < 2; ++dh) {
+                    u32x4* p = reinterpret_cast<u32x4*>(base + half * 2048 + dh * 1024);
+                    *p = keep_quads(*p, keep - half * 4, keep - 8 - half * 4);
+                }
         }
     };
 
@@ -263,33 +283,36 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
 #pragma unroll
         for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
 
-    const unsigned char* const k_lane = k_lds + n * kKRow + hi * 16;
-    const unsigned char* const v_lane = v_lds + n * kVRow + hi * 16;
+    const unsigned char* const k_lane = k_lds + n * 16 + hi * 1024;
+    const unsigned char* const v_lane = v_lds + n * 16 + hi * 2048;
 
-    // ---- prologue: K(0) into LDS ----
-    Stage stg;
+    // ---- prologue: K(0), K(1) requested and landed ----
     Pages pg;
     pages_of(0, 0, pg);
-    load_k(pg.k, stg);
-    store_k(0, stg);
-    pages_of(min(1, n_tiles - 1), 0, pg);            // what iteration 0 requests: K(1) and V(0)
+    request_k(0, pg.k);
+    pages_of(min(1, n_tiles - 1), 0, pg);
+    request_k(1, pg.k);
+    pages_of(min(2, n_tiles - 1), 0, pg);            // what iteration 0 requests: V(0) and K(2)
+    AG_WAIT_VMCNT(0);
     __syncthreads();
     f32x16 sc[2];
     bf16x8 pa[4], pb[4];
 
     // Iteration t of a wave: S(t) from K(t) (matrix); then P(t) = exp2(S(t) - m) (vector) side by side with
-    // O += V(t-1).P(t-1) (matrix).  Global loads for K(t+1) and V(t) are issued at its start and land in LDS
-    // at its end.  Every wave runs all n_tiles + 1 iterations (the barriers are workgroup-wide); the pieces a
-    // wave does not need are skipped.
+    // O += V(t-1).P(t-1) (matrix).  At its start it requests V(t) and K(t+2) (in that order: at its end it
+    // waits until only the four K(t+2) loads are outstanding, i.e. V(t) and K(t+1) have landed).  Requests are
+    // unconditional (past the last tile they repeat it into a buffer nobody reads), so the loop body has one
+    // shape.  Every wave runs all n_tiles + 1 iterations (the barriers are workgroup-wide); the pieces a wave
+    // does not need are skipped.
     auto iter = [&](int t, bf16x8 (&p_prev)[4], bf16x8 (&p_cur)[4]) {
-        // Requests are unconditional (past the last tile they repeat it into a buffer nobody reads): the
-        // loop body has one shape, so no wait is ever placed ahead of the compute on behalf of a skipped store.
-        load_k(pg.k, stg);
-        load_v(min(t, n_tiles - 1), pg.v, stg);
-        pages_of(min(t + 2, n_tiles - 1), min(t + 1, n_tiles - 1), pg);   // for the next iteration's requests
+        const int tv = min(t, n_tiles - 1);
+        Pages nxt;                                    // ids for the next iteration's requests: asked for first,
+        pages_of(min(t + 3, n_tiles - 1), min(t + 1, n_tiles - 1), nxt);   // so they never queue behind tile data
+        request_v(t & 1, pg.v);
+        request_k(t + 2, pg.k);
         const bool do_sm = t < wave_tiles, do_pv = t >= 1 && t <= wave_tiles;
-        const unsigned char* kb = k_lane + (t & 1) * kKTile;
-        const unsigned char* vb = v_lane + ((t + 1) & 1) * kVTile;
+        const unsigned char* kb = k_lane + (t % kKStages) * kTile;
+        const unsigned char* vb = v_lane + ((t + 1) & 1) * kTile;
         float mx = -INFINITY;
         if (do_sm) {
             qk_tile(kb, qf, sc);
@@ -316,7 +339,7 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
             constexpr int kAhead = AG_PREFILL_AHEAD;
             bf16x8 opnd[kAhead + 1];
             auto operand = [&](int i) -> const unsigned char* {   // order (j, mb)
-                return vb + (i & 3) * 32 * kVRow + (i >> 2) * 32;
+                return vb + (i & 3) * 512 + (i >> 2) * 4096;
             };
 #pragma unroll
             for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
@@ -351,8 +374,9 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
                 exp_tile(sc, sl2, m, lsum, p_cur);
             }
         }
-        store_k(t + 1, stg);
-        store_v(t, stg);
+        AG_WAIT_VMCNT(4);
+        scrub_v(t & 1, tv);
+        pg = nxt;
         __syncthreads();
     };
 
@@ -363,10 +387,11 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
     }
 
     // ---- normalise, transpose through LDS, store rows contiguously ----
+    AG_WAIT_VMCNT(0);                                // the last (redundant) tile requests still write to LDS
+    __syncthreads();
     lsum += __shfl_xor(lsum, 32);
     const float inv = 1.0f / lsum;
     unsigned char* ob = lds + w * (32 * 256);       // this wave's [32 rows][128 ch] bf16, rows XOR-swizzled
-    // (the barrier that closed the loop guarantees nobody still reads the K/V tiles)
 #pragma unroll
     for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
