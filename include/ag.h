@@ -32,14 +32,15 @@
  *                     channels of chunk c of slot s sit at ((c * page_size) + s) * 8,
  *                     so the 16-byte pieces that neighbouring lanes fetch for
  *                     neighbouring tokens are contiguous
- *       V pool        [num_pages][Hkv][D][page_size]  transposed (the value
- *                     product contracts over tokens, and the matrix cores
- *                     want the contracted index contiguous), and within each
- *                     aligned group of 16 slots the two middle quads are
- *                     swapped: slot s is stored at column
- *                     (s & ~12) | ((s & 8) >> 1) | ((s & 4) << 1), which is the
- *                     order the score tile leaves the tokens in a lane
- *                     (page sizes below 16 store slots in order)
+ *       V pool        [num_pages][Hkv][page_size/8][D][8]   transposed in chunks of
+ *                     8 keys (the value product contracts over tokens, and the
+ *                     matrix cores want the contracted index contiguous).  Within
+ *                     each aligned group g of 16 slots, chunk 2g + h holds slots
+ *                     h*4 + {0..3} and 8 + h*4 + {0..3}, in that order: the 8
+ *                     keys a lane owns after the score product.  So slot s of
+ *                     channel c sits at ((2*(s/16) + ((s/4)&1)) * D + c) * 8 +
+ *                     (s&3) + 4*((s/8)&1).  Page sizes below 16 are stored as
+ *                     plain [D][page_size].
  *       block_tables  int32 [B][max_pages_per_seq]; logical page p of session
  *                     s lives in physical page block_tables[s][p]
  *       cu_new        int32 [B+1], cu_new[0] = 0, cu_new[s+1]-cu_new[s] = new_lens[s]
@@ -79,7 +80,7 @@ typedef enum { AG_F32 = 0, AG_BF16 = 1 } ag_dtype;
 /* Describes caller-owned device memory; plain data, read during the call only. */
 typedef struct {
     void*   k_pool;            /* device, [num_pages][num_kv_heads][head_dim/8][page_size][8] */
-    void*   v_pool;            /* device, [num_pages][num_kv_heads][head_dim][page_size], slot order as above */
+    void*   v_pool;            /* device, [num_pages][num_kv_heads][page_size/8][head_dim][8], see above */
     int32_t num_pages;
     int32_t page_size;
     int32_t num_kv_heads;

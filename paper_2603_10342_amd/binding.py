@@ -119,7 +119,9 @@ class KVCache:
         td = torch_dtype(dtype)
         mk = torch.empty if fill is None else (lambda *a, **k: torch.full(*a, fill_value=fill, **k))
         self.k_pool = mk((num_pages, num_kv_heads, head_dim // 8, page_size, 8), dtype=td, device=device)
-        self.v_pool = mk((num_pages, num_kv_heads, head_dim, page_size), dtype=td, device=device)
+        vshape = (num_pages, num_kv_heads, head_dim, page_size) if page_size < 16 else \
+                 (num_pages, num_kv_heads, page_size // 8, head_dim, 8)
+        self.v_pool = mk(vshape, dtype=td, device=device)
         self.num_pages, self.page_size = num_pages, page_size
         self.num_kv_heads, self.head_dim, self.dtype = num_kv_heads, head_dim, dtype
 
@@ -133,12 +135,17 @@ class KVCache:
                                                            self.head_dim)
 
     def v_pool_token_major(self) -> torch.Tensor:
-        """The value pool as [page][head][slot][d] (the library stores [d][column], slot s in column
-        (s & ~12) | ((s & 8) >> 1) | ((s & 4) << 1) for page sizes of 16 and more)."""
+        """The value pool as [page][head][slot][d].  The library stores page sizes >= 16 as [slot chunk][d][8 keys]
+        with chunk 2g + h of each 16-slot group g holding slots h*4 + {0..3}, 8 + h*4 + {0..3}; smaller pages
+        as [d][slot]."""
         ps = self.page_size
+        if ps < 16:
+            return self.v_pool.transpose(2, 3)
         s = torch.arange(ps, device=self.v_pool.device)
-        col = s if ps < 16 else (s & ~12) | ((s & 8) >> 1) | ((s & 4) << 1)
-        return self.v_pool.index_select(3, col).transpose(2, 3)
+        chunk = ((s >> 4) << 1) | ((s >> 2) & 1)
+        pos = (s & 3) | (((s >> 3) & 1) << 2)
+        flat = self.v_pool.permute(0, 1, 2, 4, 3).reshape(self.num_pages, self.num_kv_heads, ps, self.head_dim)
+        return flat.index_select(2, chunk * 8 + pos)
 
 
 def ag_kv_append(cache: KVCache, k_new, v_new, block_tables, prefix_lens, new_lens, cu_new, total_new: int,

@@ -9,13 +9,23 @@
 
 namespace ag {
 
-// Column of slot s inside a value-page row: the two middle quads of every aligned 16 are swapped.
-__host__ __device__ inline int v_col(int slot, int ps) { return ps < 16 ? slot : ((slot & ~12) | ((slot & 8) >> 1) | ((slot & 4) << 1)); }
+// Element offset of (slot, channel) inside one (page, head) block of the value pool.  Page sizes of 16 and
+// more are stored as chunks of 8 keys, [chunk][channel][8 keys]: chunk = 2 * (slot / 16) + ((slot / 4) & 1)
+// and the position inside it is (slot & 3) + 4 * ((slot / 8) & 1), i.e. chunk 2g + h of a 16-slot group g
+// holds slots h*4 + {0..3} and 8 + h*4 + {0..3}: the 8 keys one lane owns after the score product.  Smaller
+// pages are plain [channel][slot].
+__host__ __device__ inline int64_t v_offset(int slot, int ch, int ps, int d)
+{
+    if (ps < 16) return (int64_t)ch * ps + slot;
+    const int chunk = ((slot >> 4) << 1) | ((slot >> 2) & 1);
+    const int pos = (slot & 3) | (((slot >> 3) & 1) << 2);
+    return ((int64_t)chunk * d + ch) * 8 + pos;
+}
 
 // Host-validated view of an ag_kv_cache.
 struct CacheView {
     void* k;          // [num_pages][hkv][d/8][ps][8]
-    void* v;          // [num_pages][hkv][d][ps], columns permuted by v_col
+    void* v;          // [num_pages][hkv][ps/8][d][8], see v_offset
     int num_pages, ps, ps_shift, hkv, d, dtype;
 };
 

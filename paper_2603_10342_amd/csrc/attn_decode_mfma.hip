@@ -115,11 +115,11 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
     // Row r of the first score product is slot (r & 7) of page (r >> 3) of the step; the second product takes
     // slots 8..15.  K page layout [chunk][slot][8]: lanes r = 0..7 of one lane group read 128 contiguous bytes.
     // Lane group c then owns slots (c&1)*4 + {0..3} and 8 + (c&1)*4 + {0..3} of page (c >> 1): exactly the 8
-    // columns at offset (c&1)*8 of a value-page row (see v_col), so its 16-byte V load is its P operand's partner.
+    // keys of chunk (c&1) of that value page (see v_offset), so its 16-byte V load is its P operand's partner.
     const int k_pg = r >> 3;
     const int k_off = (c * PS + (r & 7)) * 8;            // + kk * 4 * PS * 8 per k-step; + 8 * 8 for slots 8..15
     const int v_pg = c >> 1;
-    const int v_off = r * PS + (c & 1) * 8;              // + mb * 16 * PS per channel block
+    const int v_off = ((c & 1) * D + r) * 8;             // value page [half][channel][8 keys]; + mb * 16 * 8 per block
 
     auto load_step = [&](int st, StepRegs& x) {
         const int64_t pA = __builtin_amdgcn_readlane(my_pid, 2 * st);
@@ -132,7 +132,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
             x.k2[kk] = ld16(kp + kk * 4 * PS * 8 + 64);
         }
 #pragma unroll
-        for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16(vp + mb * 16 * PS);
+        for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16(vp + mb * 16 * 8);
     };
 
     auto compute_step = [&](int st, StepRegs& x) {

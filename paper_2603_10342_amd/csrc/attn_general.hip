@@ -98,11 +98,11 @@ __global__ __launch_bounds__(256) void attn_general_kernel(AttnArgs a)
             const float pj = __shfl(p, jj);
             const int64_t pg = __shfl((int)page, jj);
             const int sl = __shfl(slot, jj);
-            const T* vr = vp + (pg * hkv + g) * (int64_t)D * ps + v_col(sl, ps);
+            const T* vr = vp + (pg * hkv + g) * (int64_t)D * ps;
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 const int d = lane + 64 * c;
-                if (d < D) o[c] = fmaf(pj, to_f32(vr[(int64_t)d * ps]), o[c]);
+                if (d < D) o[c] = fmaf(pj, to_f32(vr[v_offset(sl, d, ps, D)]), o[c]);
             }
         }
         m = m_new;

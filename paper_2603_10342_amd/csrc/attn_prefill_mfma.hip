@@ -249,14 +249,14 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
 #pragma unroll
         for (int i = 0; i < 4; ++i) load_to_lds(src + i * 256, dst + i * 1024);
     };
-    // V(tv): wave w moves page w: instruction (half, dh) moves the 16-byte half `half` of 64 channel rows.
+    // V(tv): wave w moves page w, whose [half][channel][8 keys] layout is the LDS layout: four 1 KiB runs.
     auto request_v = [&](int stage, int pid) {
-        const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 32;
+        const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 16;
         const unsigned dst = lds_address(v_lds) + stage * kTile + (2 * wu) * 2048;
 #pragma unroll
         for (int half = 0; half < 2; ++half)
 #pragma unroll
-            for (int dh = 0; dh < 2; ++dh) load_to_lds(src + dh * 64 * 32 + half * 16, dst + half * 2048 + dh * 1024);
+            for (int dh = 0; dh < 2; ++dh) load_to_lds(src + half * 2048 + dh * 1024, dst + half * 2048 + dh * 1024);
     };
     // Slots of the session's last page that hold no token may contain anything (NaN included) and would poison
     // the value product even under a zero weight: once V(tv) has landed, zero them in LDS.

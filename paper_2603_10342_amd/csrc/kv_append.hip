@@ -5,7 +5,7 @@
 // Append is an index map plus a bit-exact copy: new token i of session s goes
 // to logical position P_s + i -> page bt[s][pos / ps], slot pos % ps.
 //   K page  [D/8][slot][8] : chunk-major; a token's row is cut into 8-channel chunks
-//   V page  [D][slot']     : transposed, slots in the order v_col() gives
+//   V page  [slot/8'][D][8]: transposed in chunks of 8 keys, see v_offset()
 // 16 neighbouring lanes hold 16 consecutive tokens of one chunk of D, so each
 // store instruction writes runs of neighbouring slots.
 // One workgroup of 256 threads takes 16 consecutive rows of the token-major
@@ -69,12 +69,12 @@ __global__ __launch_bounds__(256) void kv_append_kernel(E* __restrict__ k_pool, 
         const int slot = s_slot[tok];
         const int64_t row = (int64_t)(t0 + tok) * hkv + h;
         E* kdst = k_pool + ((int64_t)page * hkv + h) * d * ps + (int64_t)slot * 8;        // + chunk * ps * 8
-        E* vdst = v_pool + ((int64_t)page * hkv + h) * d * ps + v_col(slot, ps);          // + channel * ps
+        E* vdst = v_pool + ((int64_t)page * hkv + h) * d * ps;
         for (int c = tid >> 4; c < chunks; c += 16) {
             *reinterpret_cast<C8*>(kdst + (int64_t)c * ps * 8) = *reinterpret_cast<const C8*>(k_new + row * d + c * 8);
             const C8 x = *reinterpret_cast<const C8*>(v_new + row * d + c * 8);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) vdst[(int64_t)(c * 8 + e) * ps] = x.e[e];
+            for (int e = 0; e < 8; ++e) vdst[v_offset(slot, c * 8 + e, ps, d)] = x.e[e];
         }
     }
 }
