@@ -68,10 +68,4 @@ ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st);
 
 ag_status launch_probe(uint32_t* ids_out, int n_wg, int spin_cycles, hipStream_t st);
 
-// Tokens of context handled by one decode workgroup (one split).
-#ifndef AG_DECODE_SPLIT
-#define AG_DECODE_SPLIT 512
-#endif
-constexpr int kDecodeSplit = AG_DECODE_SPLIT;
-
 }  // namespace ag

@@ -9,17 +9,19 @@
 // contractions run on the matrix cores so that the vector ALUs only do the
 // softmax bookkeeping:
 //
-//   split kernel, one workgroup (4 waves) per (session, KV head, 512-token split);
-//   each wave owns 128 consecutive tokens and walks them 32 (two pages) at a time:
+//   split kernel, one workgroup (4 waves) per (session, KV head, split).  A session's context is cut into
+//   n = ceil(ctx / split size) equal parts (rounded up to 128 tokens), so no workgroup is left with a sliver;
+//   each wave owns a quarter of a part and walks it 32 tokens (two pages) at a time:
 //     S^T[token][head] = K[token][:] . Q[head][:]     2 x 4 MFMA 16x16x32 (heads padded to 16)
 //     streaming softmax on S^T (running max m, running sum l; exp2 with log2(e) folded in)
 //     O^T[d][head]    += V^T[d][token] . P^T[token][head]   8 MFMA 16x16x32
 //   K rows are loaded straight into the A-operand layout (lane = token row,
-//   16 B = 8 channels); V pages are stored transposed ([d][slot]) so a lane's
-//   16 B load is 8 consecutive tokens of one channel, which is the A operand
-//   of the second product.  The MFMA row order of the first product is
-//   chosen so that the 8 scores a lane ends up with are exactly the 8
-//   tokens its V load covers: no cross-lane shuffles between the products.
+//   16 B = 8 channels; pages are chunk-major so 8 neighbouring lanes read 128
+//   contiguous bytes); V pages are stored transposed in chunks of 8 keys, so a
+//   lane's 16 B load is 8 tokens of one channel, the A operand of the second
+//   product.  The MFMA row order of the first product is chosen so that the
+//   8 scores a lane ends up with are exactly the 8 tokens its V load covers:
+//   no cross-lane shuffles between the products.
 //   The 4 waves are merged in LDS and the workgroup writes one partial
 //   (m, l, O) per query head to the workspace;
 //
@@ -37,12 +39,17 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int PS = 16;
-constexpr int kWaveTok = kDecodeSplit / 4;   // tokens per wave
-constexpr int kSteps = kWaveTok / 32;        // two pages per step
-static_assert(kSteps >= 1 && kSteps <= 8, "a wave walks 1..8 steps of 32 tokens");
 #ifndef AG_DECODE_PREFETCH
-#define AG_DECODE_PREFETCH 1
+#define AG_DECODE_PREFETCH 0
 #endif
+
+// Tokens of one part of a session's context when it is cut for splits of at most `split` tokens:
+// n = ceil(ctx / split) equal parts, each a multiple of 128 (32 per wave step x 4 waves).
+__host__ __device__ inline int part_tokens(int ctx, int split)
+{
+    const int n = (ctx + split - 1) / split;
+    return (((ctx + n - 1) / n) + 127) & ~127;
+}
 constexpr float kLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ bf16x8 ld16(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
@@ -64,23 +71,30 @@ struct StepRegs {       // one wave's K and V operands for 32 tokens (two pages)
     bf16x8 k1[4], k2[4], v[8];
 };
 
+// kSteps: steps of 32 tokens a wave may walk; the split size is 128 * kSteps tokens.
+template <int kSteps>
 __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float* __restrict__ ws_o,
                                                               float* __restrict__ ws_ml, int n_splits_max)
 {
+    static_assert(kSteps >= 1 && kSteps <= 16, "a wave walks 1..16 steps of 32 tokens");
+    constexpr int kSplit = 128 * kSteps;
     __shared__ float s_o[4][16][D];     // per wave, per (padded) head: unnormalised O
     __shared__ float s_m[4][16];
     __shared__ float s_l[4][16];
 
     const int split = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
     const int ctx = a.ctx_lens[s];
-    const int start = split * kDecodeSplit;
-    if (start >= ctx) return;            // uniform over the workgroup; covers ctx == 0
+    if (ctx <= 0) return;
+    const int part = part_tokens(ctx, kSplit);
+    const int start = split * part;
+    if (start >= ctx) return;            // uniform over the workgroup
+    const int wave_tok = part >> 2;      // a multiple of 32, at most 32 * kSteps
 
     const int hkv = a.c.hkv, hq = a.hq;
     const int G = hq / hkv;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
-    const int wstart = start + w * kWaveTok;
+    const int wstart = start + w * wave_tok;
 
     const __bf16* kpool = (const __bf16*)a.c.k;
     const __bf16* vpool = (const __bf16*)a.c.v;
@@ -104,7 +118,7 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
         const int lp = min((wstart >> 4) + (lane & (2 * kSteps - 1)), n_pages_ctx - 1);
         my_pid = a.bt[(int64_t)s * a.max_pages + lp];
     }
-    const int n_steps = wstart < ctx ? min(kSteps, (ctx - wstart + 31) >> 5) : 0;   // uniform over the wave
+    const int n_steps = wstart < ctx ? min(wave_tok >> 5, (ctx - wstart + 31) >> 5) : 0;   // uniform over the wave
 
     const float sl2 = a.scale * kLog2e;
     float m = -INFINITY, lsum = 0.0f;
@@ -226,7 +240,8 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
 }
 
 __global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const float* __restrict__ ws_o,
-                                                           const float* __restrict__ ws_ml, int n_splits_max)
+                                                           const float* __restrict__ ws_ml, int n_splits_max,
+                                                           int split_tokens)
 {
     const int row = blockIdx.x;                 // s * hq + h
     const int s = row / a.hq;
@@ -234,7 +249,8 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const flo
     const int ctx = a.ctx_lens[s];
     __bf16* out = (__bf16*)a.out + (int64_t)row * D;
     if (ctx <= 0) { out[d] = (__bf16)0.0f; return; }
-    const int n = (ctx + kDecodeSplit - 1) / kDecodeSplit;
+    const int part = part_tokens(ctx, split_tokens);
+    const int n = (ctx + part - 1) / part;               // parts that exist, as the split kernel cuts them
     const int64_t base = (int64_t)row * n_splits_max;
     float ms = -INFINITY;
     for (int i = 0; i < n; ++i) ms = fmaxf(ms, ws_ml[(base + i) * 2]);
@@ -247,13 +263,27 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const flo
     out[d] = (__bf16)(acc / l);
 }
 
-inline int splits_for(int max_ctx) { return max_ctx <= 0 ? 1 : (max_ctx + kDecodeSplit - 1) / kDecodeSplit; }
+// Workspace is sized for the smallest split the launcher may choose.
+constexpr int kMinSplit = 256;
+inline int splits_for(int max_ctx, int split) { return max_ctx <= 0 ? 1 : (max_ctx + split - 1) / split; }
+
+// Split size for a launch: as long as possible (each workgroup pays a fixed start-up of three dependent reads)
+// while the launch still has a few workgroups per CU to balance with.  Only host-known bounds are available.
+inline int choose_split(int batch, int hkv, int max_ctx)
+{
+    const int64_t want = 4 * 256;            // workgroups, counting sessions at about 60 % of max_ctx
+    for (int split = 2048; split > kMinSplit; split >>= 1) {
+        const int64_t wgs = (int64_t)batch * hkv * ((6 * (int64_t)max_ctx / 10 + split - 1) / split);
+        if (wgs >= want) return split;
+    }
+    return kMinSplit;
+}
 
 }  // namespace
 
 size_t decode_workspace_bytes(int batch, int hq, int d, int max_ctx)
 {
-    return (size_t)batch * hq * splits_for(max_ctx) * (size_t)(d + 2) * sizeof(float);
+    return (size_t)batch * hq * splits_for(max_ctx, kMinSplit) * (size_t)(d + 2) * sizeof(float);
 }
 
 bool decode_mfma_supported(const AttnArgs& a)
@@ -264,18 +294,25 @@ bool decode_mfma_supported(const AttnArgs& a)
 
 ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
-    const int nsm = splits_for(a.max_ctx);
+    const int split = choose_split(a.batch, a.c.hkv, a.max_ctx);
+    const int nsm = splits_for(a.max_ctx, split);
     float* ws_o = (float*)ws;
     float* ws_ml = ws_o + (size_t)a.batch * a.hq * nsm * D;
     if (a.batch > 65535 || a.c.hkv > 65535) { set_error("batch or KV heads beyond one launch grid"); return AG_ERR_INVALID_ARG; }
     if (a.max_ctx > 0) {
+        const dim3 grid(nsm, a.c.hkv, a.batch);
         prof_before(st);
-        hipLaunchKernelGGL(decode_split_kernel, dim3(nsm, a.c.hkv, a.batch), dim3(256), 0, st, a, ws_o, ws_ml, nsm);
+        switch (split) {
+            case 2048: hipLaunchKernelGGL(decode_split_kernel<16>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
+            case 1024: hipLaunchKernelGGL(decode_split_kernel<8>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
+            case 512:  hipLaunchKernelGGL(decode_split_kernel<4>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
+            default:   hipLaunchKernelGGL(decode_split_kernel<2>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
+        }
         prof_after(st);
         ag_status e = hip_check(hipGetLastError(), "decode split launch");
         if (e) return e;
     }
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(a.batch * a.hq), dim3(128), 0, st, a, ws_o, ws_ml, nsm);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(a.batch * a.hq), dim3(128), 0, st, a, ws_o, ws_ml, nsm, split);
     return hip_check(hipGetLastError(), "decode merge launch");
 }
 

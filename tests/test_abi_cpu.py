@@ -56,8 +56,8 @@ def test_null_and_shape_errors_come_from_the_host_layer():
 
 
 def test_decode_workspace_size():
-    # one (max, sum, D values) fp32 triple per (session, query head, 512-token split)
-    assert B.ag_attn_decode_workspace_bytes(64, 32, 128, 4096) == 64 * 32 * 8 * 130 * 4
+    # one (max, sum, D values) fp32 triple per (session, query head, split), sized for the smallest split (256)
+    assert B.ag_attn_decode_workspace_bytes(64, 32, 128, 4096) == 64 * 32 * 16 * 130 * 4
     assert B.ag_attn_decode_workspace_bytes(2, 4, 64, 1) == 2 * 4 * 1 * 66 * 4
     assert B.ag_attn_decode_workspace_bytes(0, 4, 64, 1) == 0
 
