@@ -38,6 +38,19 @@ def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
+def measured_traffic(key):
+    """HBM bytes per launch (read + write) that rocprofv3's FETCH_SIZE / WRITE_SIZE counters showed for a kernel on a
+    workload, from the committed summary profiles/hbm_traffic_pmc.txt (PMC runs cannot be taken inside this script)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) == 3 and f[0] == key:
+            return int(f[1]) + int(f[2])
+    return None
+
+
 def pct(xs, p):
     """Nearest-rank percentile."""
     s = sorted(xs)
@@ -149,7 +162,7 @@ def bench_decode(args, torch, B, I):
         for b in (c.fill, c.step):
             O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
         reps, t_cpu, ref = 0, 0.0, None
-        while t_cpu < 10.0 and reps < 20:
+        while t_cpu < 10.0 and reps < 400:
             t0 = time.perf_counter()
             ref = O.decode(kp, vp, g.dtype, c.step.q, c.block_tables, c.ctx_lens, g.num_q_heads, g.scale)
             t_cpu += time.perf_counter() - t0
@@ -206,7 +219,8 @@ def bench_prefill(kind, args, torch, B, I):
         "kernel_TFLOPs": flops / (prof["mean_us"] * 1e-6) / 1e12,
         "roofline": {"bound": "mfma", "achieved": flops / (prof["mean_us"] * 1e-6) / 1e12,
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / (prof["mean_us"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                     "frac": flops / (prof["mean_us"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": measured_traffic("prefill_mfma_kernel." + ("config3" if kind == "cold" else "config4"))},
     }
     log(kind, json.dumps(out))
 
@@ -418,7 +432,8 @@ def main():
         line.update({
             "value": d["step_GBps"], "ms_per_step": d["ms_per_step"],
             "roofline": {"bound": "hbm", "achieved": d["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": d["kernel_GBps"] / HBM_PEAK_GBPS, "traffic": None,
+                         "frac": d["kernel_GBps"] / HBM_PEAK_GBPS,
+                         "traffic": measured_traffic("decode_split_kernel.config2"),
                          "kernel": d["kernel"], "kernel_us": d["kernel_us"], "algorithmic_bytes": d["attn_bytes"]},
             "cpu_baseline": d.get("cpu_baseline"),
         })
