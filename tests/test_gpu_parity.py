@@ -295,3 +295,50 @@ def test_host_side_errors_are_reported_before_launch():
     with pytest.raises(B.AgError):
         B.ag_debug_validate(cache, bad, d.prefix, d.new, d.cu)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ other page sizes and head dims (general kernels)
+@pytest.mark.parametrize("ps,d,dtype", [(1, 64, I.F32), (4, 64, I.BF16), (8, 128, I.BF16), (32, 64, I.F32),
+                                        (64, 128, I.BF16), (16, 256, I.BF16), (16, 8, I.F32)])
+def test_general_kernels_cover_other_page_sizes_and_head_dims(ps, d, dtype):
+    """Pool layouts depend on the page size (chunks of 8 keys from 16 slots up, plain below): append must stay
+    bit-exact and all three classes must match the oracle for every supported combination."""
+    lens_a, lens_b = [37, 5, 64], [20, 70, 1]
+    pages = sum((a + b + 1 + ps - 1) // ps for a, b in zip(lens_a, lens_b)) + 3
+    g = I.Geometry(4, 2, d, ps, pages, dtype)
+    bt = I.deal_block_tables(I.rng_for(23, 0), [a + b + 1 for a, b in zip(lens_a, lens_b)], ps, pages)
+    cold = make_batch(g, [0, 0, 0], lens_a, seed=23, bt=bt)
+    res = make_batch(g, lens_a, lens_b, seed=23, bt=bt, stream=2)
+    dec = make_batch(g, [a + b for a, b in zip(lens_a, lens_b)], [1, 1, 1], seed=23, bt=bt, stream=3)
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    for b, kind in [(cold, "cold"), (res, "resume"), (dec, "decode")]:
+        got, ref = run_phase(cache, kp, vp, b, kind)
+        check_close(got, ref, dtype, f"{kind} ps={ps} d={d}")
+    pools_match(cache, kp, vp, dtype)
+
+
+def test_decode_with_more_than_16_heads_per_kv_head_uses_the_general_kernel():
+    g = I.Geometry(32, 1, 128, 16, 64, I.BF16)
+    c = I.make_decode(batch=3, lo=20, hi=300, num_pages=64, geom=g, seed=29, sigma_qk=1.0, sigma_v=1.0)
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    gpu_append(cache, DevBatch(c.fill))
+    oracle_append(kp, vp, c.fill)
+    got, ref = run_phase(cache, kp, vp, c.step, "decode")
+    check_close(got, ref, g.dtype, "decode G=32")
+
+
+def test_long_context_decode_uses_the_longest_split():
+    """One session of 40000 tokens: 2048-token splits, many partials to merge, page ids far apart."""
+    g = slm(pages=2600, hq=8, hkv=2)
+    ctx = np.array([40000, 129], np.int32)
+    bt = I.deal_block_tables(I.rng_for(31, 0), ctx, 16, g.num_pages)
+    fill = make_batch(g, [0, 0], ctx - 1, seed=31, bt=bt, sigma_qk=1.0, sigma_v=1.0)
+    step = make_batch(g, ctx - 1, [1, 1], seed=31, bt=bt, stream=2, sigma_qk=1.0, sigma_v=1.0)
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    gpu_append(cache, DevBatch(fill))
+    oracle_append(kp, vp, fill)
+    got, ref = run_phase(cache, kp, vp, step, "decode")
+    check_close(got, ref, g.dtype, "decode 40000")
