@@ -47,6 +47,7 @@ namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -140,17 +141,21 @@ __device__ __forceinline__ float row_max(const f32x16 (&sc)[2])
     return mx;
 }
 
-// P^T = exp2(S^T * sl2 - m) packed as the B operands of the four k-steps of the second product; adds to lsum.
+// P^T = exp2(S^T * sl2 - m) packed as the B operands of the four k-steps of the second product; adds to lsum
+// the weights as rounded to bf16 (what the value product multiplies by), one dot2 per packed pair.
 __device__ __forceinline__ void exp_tile(const f32x16 (&sc)[2], float sl2, float m, float& lsum, bf16x8 (&pb)[4])
 {
+    const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
     float psum = 0.f;
 #pragma unroll
     for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(sc[b][i], sl2, -m));
-            psum += p;
-            pb[b * 2 + (i >> 3)][i & 7] = (__bf16)p;
+        for (int i = 0; i < 16; i += 2) {
+            const bf16x2 pr = {(__bf16)__builtin_amdgcn_exp2f(fmaf(sc[b][i], sl2, -m)),
+                               (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[b][i + 1], sl2, -m))};
+            psum = __builtin_amdgcn_fdot2_f32_bf16(pr, kOnes, psum, false);
+            pb[b * 2 + (i >> 3)][i & 7] = pr[0];
+            pb[b * 2 + (i >> 3)][(i & 7) + 1] = pr[1];
         }
     lsum += psum;
 }
@@ -343,6 +348,7 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
             };
 #pragma unroll
             for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
+            const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
             float psum = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
@@ -351,9 +357,10 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
                 const int e = 2 * i;
                 const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][e & 15], sl2, -m));
                 const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][(e & 15) + 1], sl2, -m));
-                psum += p0 + p1;
-                p_cur[e >> 3][e & 7] = (__bf16)p0;
-                p_cur[e >> 3][(e & 7) + 1] = (__bf16)p1;
+                const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, kOnes, psum, false);   // l sums the weights as rounded
+                p_cur[e >> 3][e & 7] = pr[0];
+                p_cur[e >> 3][(e & 7) + 1] = pr[1];
                 __builtin_amdgcn_sched_barrier(0);
             }
             lsum += psum;
