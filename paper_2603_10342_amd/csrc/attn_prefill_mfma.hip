@@ -53,7 +53,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int PS = 16;
-constexpr int BM = 128;                 // query rows per workgroup
 constexpr int BN = 64;                  // keys per tile
 // LDS tiles are chunk-major, like the pages themselves, and are filled by direct global-to-LDS loads:
 //   K tile [chunk c = 0..15][key 0..63][8 ch]   operand of key n, chunk c at (c * 64 + n) * 16 bytes
@@ -63,8 +62,11 @@ constexpr int BN = 64;                  // keys per tile
 // is the lane's base plus a compile-time offset.
 constexpr int kTile = BN * D * 2;       // 16 KiB, K and V alike
 constexpr int kKStages = 3;             // K(t+2) is requested while K(t) is used
-constexpr int kVStages = 2;             // V(t) is requested while V(t-1) is used
-constexpr int kLdsBytes = (kKStages + kVStages) * kTile;   // 80 KiB: two workgroups per CU
+// V stages: 2 (V(t) requested while V(t-1) is used).  A third stage (V(t+1) requested an iteration earlier) is
+// supported by the loop but measured no faster, so both workgroup shapes use 80 KiB: two 4-wave workgroups or
+// one 8-wave workgroup per CU.
+constexpr int v_stages(int) { return 2; }
+constexpr int lds_bytes(int nw) { return (kKStages + v_stages(nw)) * kTile; }
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may grow before O is rescaled
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -178,9 +180,16 @@ __device__ __forceinline__ unsigned lds_address(const void* p)
 // s_waitcnt vmcnt(n) alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4, lgkmcnt 11:8 left at maximum).
 #define AG_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(((n) & 0xF) | (((n) >> 4) << 14) | (7 << 4) | (0xF << 8))
 
-__global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int q_tiles,
-                                                                                      int per_xcd, int64_t total_work)
+// NW waves per workgroup (4 or 8), 32 query rows each.  Eight waves halve the K/V bytes moved per flop (a tile
+// is shared by twice the rows) at the price of coarser query tiles.
+template <int NW>
+__global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int q_tiles,
+                                                                                         int per_xcd, int64_t total_work)
 {
+    constexpr int BM = 32 * NW;             // query rows per workgroup
+    constexpr int kPer = 16 / NW;           // direct-load instructions per wave for a K tile, and for a V tile
+    constexpr int kVStages = v_stages(NW);
+    constexpr int kVLead = kVStages - 2;    // V(t + kVLead) is requested in iteration t
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
 
     // ---- which (session, head, query tile) ----
@@ -234,48 +243,49 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
 
     // ---- tile requests: direct global-to-LDS loads, 4 + 4 wave-wide instructions per wave and tile ----
     unsigned char* const k_lds = lds;                       // K tile t lives at k_lds + (t % 3) * kTile
-    unsigned char* const v_lds = lds + kKStages * kTile;    // V tile t lives at v_lds + (t & 1) * kTile
+    unsigned char* const v_lds = lds + kKStages * kTile;    // V tile t lives at v_lds + (t % kVStages) * kTile
     const int kpg = lane >> 4, kslot = lane & 15;           // K: lane = key of the tile (page, slot)
 
     // Physical pages of a tile, through scalar loads (the index is uniform), fetched one iteration before the
     // tile's data is requested, so no data request ever waits for a block-table read.
     struct Pages { int k[4]; int v; };
+    const int v_page = (wu * kPer) / 4;                        // page of a V tile this wave brings in (4 runs per page)
     auto pages_of = [&](int tk, int tv, Pages& pg) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) pg.k[i] = bt[min(tk * 4 + i, last_page)];
-        pg.v = bt[min(tv * 4 + wu, last_page)];              // wave w brings in page w of the V tile
+        pg.v = bt[min(tv * 4 + v_page, last_page)];
     };
-    // K(tk): instruction i of wave w moves chunk c = 4w + i of all 64 keys: four 256-byte runs, one per page.
+    // K(tk): instruction i of wave w moves chunk c = kPer*w + i of all 64 keys: four 256-byte runs, one per page.
     auto request_k = [&](int tk, const int (&pid)[4]) {
         const int mine = kpg == 0 ? pid[0] : kpg == 1 ? pid[1] : kpg == 2 ? pid[2] : pid[3];
         const unsigned char* src = (const unsigned char*)kpool + ((int64_t)mine * hkv + g) * (int64_t)(D * PS * 2) +
-                                   (wu * 4) * 256 + kslot * 16;
-        const unsigned dst = lds_address(k_lds) + (tk % kKStages) * kTile + (wu * 4) * 1024;
+                                   (wu * kPer) * 256 + kslot * 16;
+        const unsigned dst = lds_address(k_lds) + (tk % kKStages) * kTile + (wu * kPer) * 1024;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_to_lds(src + i * 256, dst + i * 1024);
+        for (int i = 0; i < kPer; ++i) load_to_lds(src + i * 256, dst + i * 1024);
     };
-    // V(tv): wave w moves page w, whose [half][channel][8 keys] layout is the LDS layout: four 1 KiB runs.
+    // V(tv): a page's [half][channel][8 keys] layout is the LDS layout, so a V tile is sixteen 1 KiB runs;
+    // wave w moves runs kPer*w .. kPer*w + kPer - 1, all of page v_page.
+    constexpr int v_runs_per_page = 4;
     auto request_v = [&](int stage, int pid) {
-        const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 16;
-        const unsigned dst = lds_address(v_lds) + stage * kTile + (2 * wu) * 2048;
+        const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) +
+                                   ((wu * kPer) % v_runs_per_page) * 1024 + lane * 16;
+        const unsigned dst = lds_address(v_lds) + stage * kTile + (wu * kPer) * 1024;
 #pragma unroll
-        for (int half = 0; half < 2; ++half)
-#pragma unroll
-            for (int dh = 0; dh < 2; ++dh) load_to_lds(src + half * 2048 + dh * 1024, dst + half * 2048 + dh * 1024);
+        for (int i = 0; i < kPer; ++i) load_to_lds(src + i * 1024, dst + i * 1024);
     };
     // Slots of the session's last page that hold no token may contain anything (NaN included) and would poison
     // the value product even under a zero weight: once V(tv) has landed, zero them in LDS.
     auto scrub_v = [&](int stage, int tv) {
-        const int keep = ctx - (tv * BN + w * PS);              // slots < keep of this wave's page hold tokens
+        const int keep = ctx - (tv * BN + v_page * PS);         // slots < keep of this wave's page hold tokens
         if (keep < PS) {                                        // uniform over the wave
-            unsigned char* base = v_lds + stage * kTile + (2 * w) * 2048 + lane * 16;
 #pragma unroll
-            for (int half = 0; half < 2; ++half)
-#pragma unroll
-                for (int dh = 0; dh < 2; ++dh) {
-                    u32x4* p = reinterpret_cast<u32x4*>(base + half * 2048 + dh * 1024);
-                    *p = keep_quads(*p, keep - half * 4, keep - 8 - half * 4);
-                }
+            for (int i = 0; i < kPer; ++i) {
+                const int run = (wu * kPer) % v_runs_per_page + i;      // run = 2 * half + (channels 64..127)
+                const int half = run >> 1;
+                u32x4* p = reinterpret_cast<u32x4*>(v_lds + stage * kTile + (wu * kPer + i) * 1024 + lane * 16);
+                *p = keep_quads(*p, keep - half * 4, keep - 8 - half * 4);
+            }
         }
     };
 
@@ -297,27 +307,31 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
     request_k(0, pg.k);
     pages_of(min(1, n_tiles - 1), 0, pg);
     request_k(1, pg.k);
-    pages_of(min(2, n_tiles - 1), 0, pg);            // what iteration 0 requests: V(0) and K(2)
+    if (kVLead) {                                    // V(0) too when iteration t requests V(t + 1)
+        pages_of(0, 0, pg);
+        request_v(0, pg.v);
+    }
+    pages_of(min(2, n_tiles - 1), min(kVLead, n_tiles - 1), pg);   // what iteration 0 requests: V(kVLead) and K(2)
     AG_WAIT_VMCNT(0);
     __syncthreads();
     f32x16 sc[2];
     bf16x8 pa[4], pb[4];
 
     // Iteration t of a wave: S(t) from K(t) (matrix); then P(t) = exp2(S(t) - m) (vector) side by side with
-    // O += V(t-1).P(t-1) (matrix).  At its start it requests V(t) and K(t+2) (in that order: at its end it
-    // waits until only the four K(t+2) loads are outstanding, i.e. V(t) and K(t+1) have landed).  Requests are
-    // unconditional (past the last tile they repeat it into a buffer nobody reads), so the loop body has one
+    // O += V(t-1).P(t-1) (matrix).  At its start it requests V(t) and then K(t+2); at its end it waits until only
+    // its own K(t+2) loads (and, with three V stages, V(t+1)) are outstanding, i.e. V(t) and K(t+1) have landed.
+    // Requests are unconditional (past the last tile they repeat it into a buffer nobody reads), so the loop body has one
     // shape.  Every wave runs all n_tiles + 1 iterations (the barriers are workgroup-wide); the pieces a wave
     // does not need are skipped.
     auto iter = [&](int t, bf16x8 (&p_prev)[4], bf16x8 (&p_cur)[4]) {
-        const int tv = min(t, n_tiles - 1);
-        Pages nxt;                                    // ids for the next iteration's requests: asked for first,
-        pages_of(min(t + 3, n_tiles - 1), min(t + 1, n_tiles - 1), nxt);   // so they never queue behind tile data
-        request_v(t & 1, pg.v);
+        const int tv = min(t, n_tiles - 1);          // the V tile that must have landed when this iteration ends
+        Pages nxt;                                    // ids for the next iteration's requests
+        pages_of(min(t + 3, n_tiles - 1), min(t + 1 + kVLead, n_tiles - 1), nxt);
+        request_v((t + kVLead) % kVStages, pg.v);
         request_k(t + 2, pg.k);
         const bool do_sm = t < wave_tiles, do_pv = t >= 1 && t <= wave_tiles;
         const unsigned char* kb = k_lane + (t % kKStages) * kTile;
-        const unsigned char* vb = v_lane + ((t + 1) & 1) * kTile;
+        const unsigned char* vb = v_lane + ((t + kVStages - 1) % kVStages) * kTile;   // V(t-1)
         float mx = -INFINITY;
         if (do_sm) {
             qk_tile(kb, qf, sc);
@@ -381,8 +395,8 @@ __global__ __launch_bounds__(256, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_k
                 exp_tile(sc, sl2, m, lsum, p_cur);
             }
         }
-        AG_WAIT_VMCNT(4);
-        scrub_v(t & 1, tv);
+        AG_WAIT_VMCNT(kPer * (1 + kVLead));
+        scrub_v(t % kVStages, tv);
         pg = nxt;
         __syncthreads();
     };
@@ -433,25 +447,38 @@ bool prefill_mfma_supported(const AttnArgs& a)
            (((uintptr_t)a.q | (uintptr_t)a.out | (uintptr_t)a.c.k | (uintptr_t)a.c.v) % 16 == 0);
 }
 
-ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
+template <int NW>
+static ag_status launch_prefill_nw(const AttnArgs& a, hipStream_t st)
 {
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load()) {
-        ag_status e = hip_check(hipFuncSetAttribute((const void*)prefill_mfma_kernel,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes),
+        ag_status e = hip_check(hipFuncSetAttribute((const void*)prefill_mfma_kernel<NW>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(NW)),
                                 "hipFuncSetAttribute(prefill)");
         if (e) return e;
         attr_set.store(true);
     }
+    constexpr int BM = 32 * NW;
     const int q_tiles = (a.max_new + BM - 1) / BM;
     const int64_t total = (int64_t)a.batch * a.hq * q_tiles;
     const int64_t per_xcd = (total + 7) / 8;
     if (per_xcd * 8 > 0x7fffffff) { set_error("too many query tiles for one launch"); return AG_ERR_INVALID_ARG; }
     prof_before(st);
-    hipLaunchKernelGGL(prefill_mfma_kernel, dim3((unsigned)(per_xcd * 8)), dim3(256), kLdsBytes, st, a, q_tiles,
+    hipLaunchKernelGGL(prefill_mfma_kernel<NW>, dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), lds_bytes(NW), st, a, q_tiles,
                        (int)per_xcd, total);
     prof_after(st);
     return hip_check(hipGetLastError(), "prefill launch");
+}
+
+ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
+{
+#ifdef AG_PREFILL_FORCE_NW
+    return launch_prefill_nw<AG_PREFILL_FORCE_NW>(a, st);
+#else
+    // 256-row tiles when chunks are long enough to fill them (a K/V tile then feeds twice the rows);
+    // 128-row tiles keep short, ragged chunks efficient
+    return a.max_new >= 512 ? launch_prefill_nw<8>(a, st) : launch_prefill_nw<4>(a, st);
+#endif
 }
 
 }  // namespace ag
