@@ -84,8 +84,21 @@ class Dev:
         self.i32 = i32
 
 
+def settle(torch, step, seconds=0.3):
+    """Untimed: run the step until the device has been busy for a while, so clocks and caches are in the state
+    sustained serving sees (the first tens of milliseconds after an idle period run measurably slower)."""
+    t0 = time.perf_counter()
+    i = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(8):
+            step(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
 def time_steps(torch, step, steps, warmup, stream=None):
     """W untimed steps, then exactly K steps between two synchronisations.  Returns seconds per step."""
+    settle(torch, step)
     for i in range(warmup):
         step(i)
     torch.cuda.synchronize()
@@ -184,7 +197,7 @@ def bench_decode(args, torch, B, I):
 
 # --------------------------------------------------------------------------- prefill (configs 3, 4)
 def bench_prefill(kind, args, torch, B, I):
-    steps, warmup = max(5, args.steps // 10), max(2, args.warmup // 5)
+    steps, warmup = max(5, args.steps // 4), max(2, args.warmup // 2)
     if kind == "cold":
         b = I.make_cold()
         g = b.geom
