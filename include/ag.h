@@ -96,6 +96,7 @@ typedef struct {
  * logical position prefix_lens[s] + i for every KV head.  Bit-exact copy.
  * total_new = cu_new[batch] is the host-side bound that sizes the launch.
  * Two sessions appending to the same physical page is a caller error.
+ * k_new, v_new and both pools must be 16-byte aligned.
  */
 AG_API ag_status ag_kv_append(const ag_kv_cache* cache,
                        const void* k_new, const void* v_new,             /* device [T][Hkv][D] */

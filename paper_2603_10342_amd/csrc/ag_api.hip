@@ -152,6 +152,10 @@ ag_status ag_kv_append(const ag_kv_cache* cache, const void* k_new, const void* 
         set_error("batch=%d max_pages_per_seq=%d total_new=%d: sizes must be positive", batch, max_pages_per_seq, total_new);
         return AG_ERR_INVALID_ARG;
     }
+    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)c.k | (uintptr_t)c.v) % 16) {
+        set_error("k_new, v_new and the pools must be 16-byte aligned");
+        return AG_ERR_INVALID_ARG;
+    }
     if (total_new == 0) return AG_OK;
     return launch_kv_append(c, k_new, v_new, block_tables, max_pages_per_seq, prefix_lens, new_lens, cu_new, batch,
                             total_new, (hipStream_t)stream);
