@@ -382,6 +382,73 @@ def bench_mixed(args, torch, B, I, info):
     return out
 
 
+# --------------------------------------------------------------------------- CU-share profile (Fig. 3 analogue)
+def bench_cushare(args, torch, B, I, info):
+    """Throughput of the three request classes alone on R CUs per XCD, R = 1..32: the MI355X analogue of the
+    paper's throughput-versus-SM-share profile (Sec. II-C, Fig. 3), the input of its allocation rule
+    R* = min{R : mu_D(R) >= r_min} (Sec. III-B)."""
+    total_cus, n_xcd = info["num_cus"], info["num_xcd"] or 8
+    per = total_cus // n_xcd
+    shares = [r for r in (1, 2, 4, 6, 8, 12, 16, 20, 24, 28, 32) if r <= per]
+
+    dc = I.make_decode()
+    g = dc.geom
+    cache_d = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+    dfill, dstep = Dev(dc.fill, torch), Dev(dc.step, torch)
+    B.ag_kv_append(cache_d, dfill.k_new, dfill.v_new, dfill.bt, dfill.prefix, dfill.new, dfill.cu, dfill.total)
+    del dfill
+    ws = torch.empty(B.ag_attn_decode_workspace_bytes(dstep.b.batch, g.num_q_heads, g.head_dim, dstep.max_ctx) // 4,
+                     dtype=torch.float32, device="cuda")
+    cold = Dev(I.make_cold(), torch)
+    cache_c = B.KVCache(cold.g.num_pages, 16, 8, 128, I.BF16, fill=0.0)
+    rc = I.make_resume()
+    cache_r = B.KVCache(rc.geom.num_pages, 16, 8, 128, I.BF16, fill=0.0)
+    rfill, res = Dev(rc.fill, torch), Dev(rc.chunk, torch)
+    B.ag_kv_append(cache_r, rfill.k_new, rfill.v_new, rfill.bt, rfill.prefix, rfill.new, rfill.cu, rfill.total)
+    del rfill
+    torch.cuda.synchronize()
+
+    def decode(st):
+        B.ag_kv_append(cache_d, dstep.k_new, dstep.v_new, dstep.bt, dstep.prefix, dstep.new, dstep.cu, dstep.total, stream=st)
+        B.ag_attn_decode(cache_d, dstep.q, dstep.out, dstep.bt, dstep.ctx, dstep.max_ctx, g.num_q_heads, g.scale, ws, stream=st)
+
+    def coldp(st):
+        B.ag_kv_append(cache_c, cold.k_new, cold.v_new, cold.bt, cold.prefix, cold.new, cold.cu, cold.total, stream=st)
+        B.ag_attn_prefill(cache_c, cold.q, cold.out, cold.bt, cold.new, cold.cu, cold.total, cold.max_new, 32, cold.g.scale, stream=st)
+
+    def resume(st):
+        B.ag_kv_append(cache_r, res.k_new, res.v_new, res.bt, res.prefix, res.new, res.cu, res.total, stream=st)
+        B.ag_attn_resume(cache_r, res.q, res.out, res.bt, res.prefix, res.new, res.cu, res.total, res.max_new,
+                         res.max_ctx, 32, res.g.scale, stream=st)
+
+    def rate(fn, st, n):
+        ext = torch.cuda.ExternalStream(st)
+        for _ in range(2):
+            fn(st)
+        ext.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn(st)
+        ext.synchronize()
+        return n / (time.perf_counter() - t0)
+
+    out = {"cus_per_xcd": shares, "decode_steps_per_s": [], "cold_tokens_per_s": [], "resume_tokens_per_s": []}
+    for r in shares:
+        st = B.ag_stream_create_cumask(B.ag_cumask_build(total_cus, n_xcd, 0, r))
+        out["decode_steps_per_s"].append(rate(decode, st, 40))
+        out["cold_tokens_per_s"].append(rate(coldp, st, 3) * cold.total)
+        out["resume_tokens_per_s"].append(rate(resume, st, 3) * res.total)
+        B.ag_stream_destroy(st)
+        log("cushare", r, out["decode_steps_per_s"][-1], out["cold_tokens_per_s"][-1], out["resume_tokens_per_s"][-1])
+    for k in ("decode_steps_per_s", "cold_tokens_per_s", "resume_tokens_per_s"):
+        out[k.split("_")[0] + "_normalised"] = [v / out[k][-1] for v in out[k]]
+    # the paper's allocation rule on the measured decode profile: smallest share whose step rate meets a target
+    # TPOT budget tau_max (ms): r_min = 1000 / tau_max steps per second
+    out["min_share_for_tpot_ms"] = {str(tau): next((r for r, v in zip(shares, out["decode_steps_per_s"]) if v >= 1000.0 / tau), None)
+                                    for tau in (0.25, 0.5, 1.0, 2.0)}
+    return out
+
+
 def bench_copycal(args, torch):
     """A plain device-to-device copy of known size: the yardstick the FETCH_SIZE / WRITE_SIZE counters of the
     attention kernels are scaled by (run this workload under `rocprofv3 --pmc`)."""
@@ -428,6 +495,8 @@ def main():
         res["resume_prefill"] = bench_prefill("resume", args, torch, B, I)
     if "mixed" in want:
         res["mixed"] = bench_mixed(args, torch, B, I, info)
+    if "cushare" in want:
+        res["cu_share_profile"] = bench_cushare(args, torch, B, I, info)
     if "copycal" in want:
         res["copycal"] = bench_copycal(args, torch)
 
