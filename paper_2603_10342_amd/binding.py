@@ -25,13 +25,31 @@ EXPORTS = [
     "ag_stream_create_cumask", "ag_stream_destroy", "ag_cumask_build", "ag_probe_placement", "ag_device_info",
     "ag_debug_validate", "ag_prof_enable", "ag_prof_collect", "ag_prof_disable", "ag_status_string",
     "ag_last_error", "ag_version",
+    # ag_sched.h
+    "ag_ctl_create", "ag_ctl_destroy", "ag_ctl_record_decode", "ag_ctl_tick", "ag_ctl_get", "ag_ctl_classify",
+    "ag_partition_level_for", "ag_slots_create", "ag_slots_destroy", "ag_slots_count", "ag_slots_units",
+    "ag_slots_get", "ag_slots_bind", "ag_slots_current",
 ]
+
+AG_REQ_DECODE, AG_REQ_RESUME, AG_REQ_COLD = 0, 1, 2
+AG_QUEUE_DECODE, AG_QUEUE_PREFILL = 0, 1
 
 
 class AgError(RuntimeError):
     def __init__(self, status: int, message: str):
         super().__init__(f"{message} (status {status})")
         self.status = status
+
+
+class ag_ctl_params(C.Structure):
+    _fields_ = [("S", C.c_int32), ("r_base", C.c_int32), ("r_init", C.c_int32), ("b_init", C.c_int32),
+                ("delta_r", C.c_int32), ("delta_b", C.c_int32), ("b_min", C.c_int32), ("b_max", C.c_int32),
+                ("theta_low_us", C.c_double), ("theta_high_us", C.c_double)]
+
+
+class ag_ctl_state(C.Structure):
+    _fields_ = [("r_min", C.c_int32), ("b_prefill", C.c_int32), ("tpot_us", C.c_double),
+                ("intervals", C.c_int64), ("raised", C.c_int64), ("lowered", C.c_int64)]
 
 
 class ag_kv_cache(C.Structure):
@@ -69,6 +87,20 @@ def lib():
     l.ag_prof_enable.argtypes = [i32]
     l.ag_prof_collect.argtypes = [C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(i32)]
     l.ag_prof_disable.argtypes = []
+    l.ag_ctl_create.argtypes = [C.POINTER(ag_ctl_params), C.POINTER(vp)]
+    l.ag_ctl_destroy.argtypes = [vp]
+    l.ag_ctl_record_decode.argtypes = [vp, C.c_double]
+    l.ag_ctl_tick.argtypes = [vp, C.POINTER(ag_ctl_state)]
+    l.ag_ctl_get.argtypes = [vp, C.POINTER(ag_ctl_state)]
+    l.ag_ctl_classify.argtypes = [vp, i32, i32]
+    l.ag_partition_level_for.argtypes = [i32, i32, i32]
+    l.ag_slots_create.argtypes = [i32, C.POINTER(vp)]
+    l.ag_slots_destroy.argtypes = [vp]
+    l.ag_slots_count.argtypes = [vp]
+    l.ag_slots_units.argtypes = [vp]
+    l.ag_slots_get.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
+    l.ag_slots_bind.argtypes = [vp, i32, C.POINTER(i32)]
+    l.ag_slots_current.argtypes = [vp]
     for name in EXPORTS:
         if name not in ("ag_attn_decode_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
             getattr(l, name).restype = C.c_int
@@ -241,3 +273,92 @@ def ag_version() -> str:
 
 def ag_status_string(status: int) -> str:
     return lib().ag_status_string(status).decode()
+
+
+# ---- ag_sched.h: controller (Algorithm 1) and the table of pre-established partitions ----
+
+def _nonneg(v: int) -> int:
+    if v < 0:
+        raise AgError(v, lib().ag_last_error().decode())
+    return v
+
+
+class Controller:
+    """Owns an ag_ctl.  Methods are the entry points of the same name without the prefix."""
+
+    def __init__(self, **params):
+        self._p = ag_ctl_params(**params)
+        h = C.c_void_p()
+        _check(lib().ag_ctl_create(C.byref(self._p), C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h:
+            _check(lib().ag_ctl_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def record_decode(self, step_us: float):
+        _check(lib().ag_ctl_record_decode(self._h, step_us))
+
+    def _state(self, fn) -> dict:
+        st = ag_ctl_state()
+        _check(fn(self._h, C.byref(st)))
+        return {k: getattr(st, k) for k, _ in ag_ctl_state._fields_}
+
+    def tick(self) -> dict:
+        return self._state(lib().ag_ctl_tick)
+
+    def get(self) -> dict:
+        return self._state(lib().ag_ctl_get)
+
+    def classify(self, req_type: int, len_tokens: int) -> int:
+        return _nonneg(lib().ag_ctl_classify(self._h, req_type, len_tokens))
+
+
+def ag_partition_level_for(S: int, g: int, r_min: int) -> int:
+    return _nonneg(lib().ag_partition_level_for(S, g, r_min))
+
+
+class Slots:
+    """Owns an ag_slots table (CU-masked stream pairs on the current device)."""
+
+    def __init__(self, g_units: int):
+        h = C.c_void_p()
+        _check(lib().ag_slots_create(g_units, C.byref(h)))
+        self._h = h
+
+    def close(self):
+        if self._h:
+            _check(lib().ag_slots_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def count(self) -> int:
+        return _nonneg(lib().ag_slots_count(self._h))
+
+    def units(self) -> int:
+        return _nonneg(lib().ag_slots_units(self._h))
+
+    def get(self, index: int) -> dict:
+        u, d, p = C.c_int32(), C.c_void_p(), C.c_void_p()
+        _check(lib().ag_slots_get(self._h, index, C.byref(u), C.byref(d), C.byref(p)))
+        return {"decode_units": u.value, "decode_stream": int(d.value or 0), "prefill_stream": int(p.value or 0)}
+
+    def bind(self, r_min: int) -> int:
+        i = C.c_int32()
+        _check(lib().ag_slots_bind(self._h, r_min, C.byref(i)))
+        return i.value
+
+    def current(self) -> int:
+        return _nonneg(lib().ag_slots_current(self._h))

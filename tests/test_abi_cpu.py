@@ -1,5 +1,5 @@
-"""No GPU needed: the C-ABI library loads, exports every symbol include/ag.h
-declares, and its host-side checks answer before any device work."""
+"""No GPU needed: the C-ABI library loads, exports every symbol the headers under include/
+declare, and its host-side checks answer before any device work."""
 import ctypes as C
 import os
 import re
@@ -12,7 +12,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "ag.h")).read()
+    inc = os.path.join(ROOT, "include")
+    text = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     return sorted(set(re.findall(r"AG_API\s+[\w\s\*]+?\b(ag_\w+)\s*\(", text)))
 
 
@@ -33,14 +34,14 @@ def test_status_strings_and_version():
 
 def test_null_and_shape_errors_come_from_the_host_layer():
     l = B.lib()
-    ok = B.ag_kv_cache(1, 1, 8, 16, 2, 128, B.AG_BF16)          # non-null fake pointers: never dereferenced here
+    ok = B.ag_kv_cache(4096, 4096, 8, 16, 2, 128, B.AG_BF16)          # non-null fake pointers: never dereferenced here
     assert l.ag_kv_append(None, None, None, None, 1, None, None, None, 1, 1, None) == B.AG_ERR_INVALID_ARG
     assert l.ag_kv_append(C.byref(ok), None, None, None, 1, None, None, None, 1, 1, None) == B.AG_ERR_INVALID_ARG
     assert b"NULL" in l.ag_last_error()
     for field, val, want in [("dtype", 7, B.AG_ERR_UNSUPPORTED), ("head_dim", 100, B.AG_ERR_UNSUPPORTED),
                              ("head_dim", 512, B.AG_ERR_UNSUPPORTED), ("page_size", 24, B.AG_ERR_UNSUPPORTED),
                              ("num_pages", 0, B.AG_ERR_INVALID_ARG)]:
-        c = B.ag_kv_cache(1, 1, 8, 16, 2, 128, B.AG_BF16)
+        c = B.ag_kv_cache(4096, 4096, 8, 16, 2, 128, B.AG_BF16)
         setattr(c, field, val)
         assert l.ag_attn_prefill(C.byref(c), 1, 1, 1, 4, 1, 1, 1, 16, 16, 4, 0.1, None) == want, field
     # heads not a multiple, contradictory bounds, bad scale
