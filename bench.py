@@ -279,36 +279,52 @@ def placement(torch, B, stream, n_wg=4096):
     return pairs, per_xcd
 
 
-def bench_mixed(args, torch, B, I, info):
-    m = I.make_mixed()
-    g = m.geom
-    cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
-    cold, rfill, res, dfill, dec = (Dev(x, torch) for x in (m.cold, m.resume_fill, m.resume, m.decode_fill, m.decode))
-    for f in (rfill, dfill):
-        B.ag_kv_append(cache, f.k_new, f.v_new, f.bt, f.prefix, f.new, f.cu, f.total)
-    nb = dec.b.batch
-    max_ctx = dec.max_ctx
-    ws = torch.empty(B.ag_attn_decode_workspace_bytes(nb, g.num_q_heads, g.head_dim, max_ctx) // 4,
-                     dtype=torch.float32, device="cuda")
-    torch.cuda.synchronize()
-    total_cus = info["num_cus"]
-    n_xcd = info["num_xcd"] or 8
-    per = total_cus // n_xcd
-    prefill_tokens = cold.total + res.total
-    prefill_flops = m.cold.attn_flops() + m.resume.attn_flops()
-    kv_bytes = int(m.decode.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
+class MixedLoad:
+    """Config 5's two request streams on one cache: a decode batch (stream A) and a loop of cold + resume
+    prefills (stream B)."""
 
-    def decode_step(st):
-        B.ag_kv_append(cache, dec.k_new, dec.v_new, dec.bt, dec.prefix, dec.new, dec.cu, dec.total, stream=st)
-        B.ag_attn_decode(cache, dec.q, dec.out, dec.bt, dec.ctx, max_ctx, g.num_q_heads, g.scale, ws, stream=st)
+    def __init__(self, torch, B, I):
+        m = I.make_mixed()
+        g = m.geom
+        self.B, self.g, self.m = B, g, m
+        self.cache = cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+        self.cold, rfill, self.res, dfill, self.dec = (Dev(x, torch) for x in (m.cold, m.resume_fill, m.resume, m.decode_fill, m.decode))
+        for f in (rfill, dfill):
+            B.ag_kv_append(cache, f.k_new, f.v_new, f.bt, f.prefix, f.new, f.cu, f.total)
+        self.max_ctx = self.dec.max_ctx
+        self.ws = torch.empty(B.ag_attn_decode_workspace_bytes(self.dec.b.batch, g.num_q_heads, g.head_dim, self.max_ctx) // 4,
+                              dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        self.prefill_tokens = self.cold.total + self.res.total
+        self.prefill_flops = m.cold.attn_flops() + m.resume.attn_flops()
+        self.kv_bytes = int(m.decode.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
 
-    def prefill_loop(st):
+    def decode_step(self, st, n=None):
+        """One decode step of the first n sessions of the batch (all by default)."""
+        B, g, dec = self.B, self.g, self.dec
+        n = dec.b.batch if n is None else n
+        B.ag_kv_append(self.cache, dec.k_new[:n], dec.v_new[:n], dec.bt[:n], dec.prefix[:n], dec.new[:n], dec.cu[:n + 1],
+                       n, stream=st)
+        B.ag_attn_decode(self.cache, dec.q[:n], dec.out[:n], dec.bt[:n], dec.ctx[:n], self.max_ctx, g.num_q_heads, g.scale,
+                         self.ws, stream=st)
+
+    def prefill_loop(self, st):
+        B, g, cold, res, cache = self.B, self.g, self.cold, self.res, self.cache
         B.ag_kv_append(cache, cold.k_new, cold.v_new, cold.bt, cold.prefix, cold.new, cold.cu, cold.total, stream=st)
         B.ag_attn_prefill(cache, cold.q, cold.out, cold.bt, cold.new, cold.cu, cold.total, cold.max_new,
                           g.num_q_heads, g.scale, stream=st)
         B.ag_kv_append(cache, res.k_new, res.v_new, res.bt, res.prefix, res.new, res.cu, res.total, stream=st)
         B.ag_attn_resume(cache, res.q, res.out, res.bt, res.prefix, res.new, res.cu, res.total, res.max_new,
                          res.max_ctx, g.num_q_heads, g.scale, stream=st)
+
+
+def bench_mixed(args, torch, B, I, info):
+    load = MixedLoad(torch, B, I)
+    decode_step, prefill_loop = load.decode_step, load.prefill_loop
+    prefill_tokens, prefill_flops, kv_bytes = load.prefill_tokens, load.prefill_flops, load.kv_bytes
+    total_cus = info["num_cus"]
+    n_xcd = info["num_xcd"] or 8
+    per = total_cus // n_xcd
 
     def run(dstream, pstream, steps, warm=100):
         """Decode steps (one host sync each, as a real decode loop has) with an optional prefill loop beside."""
@@ -382,6 +398,127 @@ def bench_mixed(args, torch, B, I, info):
     return out
 
 
+# --------------------------------------------------------------------------- closed loop (Algorithm 1)
+def bench_controller(args, torch, B, I, info):
+    """Config 5's load under the TPOT-driven controller (paper Sec. III-B, Algorithm 1) and the table of
+    pre-established partitions (Sec. III-C): a decode thread and a prefill thread submit to the streams of the
+    currently bound entry; the scheduler closes a control interval every dt, moves R_min / B_prefill and
+    rebinds.  Reports the trajectory, where it settles, and what a rebinding costs."""
+    load = MixedLoad(torch, B, I)
+    g_units = 4
+    slots = B.Slots(g_units)
+    S = slots.units()
+    entries = [slots.get(i) for i in range(slots.count())]
+    old_si = sys.getswitchinterval()
+    sys.setswitchinterval(1e-5)
+    out = {"g_units": g_units, "S": S, "entries": [e["decode_units"] for e in entries]}
+    try:
+        # reference: decode alone on the whole device, same loop shape
+        lat = []
+        for i in range(300):
+            t0 = time.perf_counter()
+            load.decode_step(None)
+            torch.cuda.current_stream().synchronize()
+            if i >= 100:
+                lat.append((time.perf_counter() - t0) * 1e6)
+        alone = pct(lat, 50)
+        params = dict(S=S, r_base=g_units, r_init=g_units, b_init=512, delta_r=g_units, delta_b=128, b_min=128,
+                      b_max=1024, theta_low_us=1.2 * alone, theta_high_us=1.5 * alone)
+        ctl = B.Controller(**params)
+        dt = args.ctl_interval_ms / 1e3
+        stop = threading.Event()
+        cur = [slots.bind(params["r_init"])]
+        nsess = [load.dec.b.batch]                  # sessions decoding: all in the first half, a quarter afterwards
+        dec_lat, dec_after_rebind = [], []
+        loops, held = [0], [0]
+
+        def decode_thread():
+            last = -1
+            while not stop.is_set():
+                i = cur[0]
+                st = entries[i]["decode_stream"]
+                t0 = time.perf_counter()
+                load.decode_step(st, nsess[0])
+                torch.cuda.ExternalStream(st).synchronize()
+                us = (time.perf_counter() - t0) * 1e6
+                ctl.record_decode(us)
+                (dec_after_rebind if (i != last and last >= 0) else dec_lat).append((i, us))
+                last = i
+
+        def prefill_thread():
+            while not stop.is_set():
+                st = entries[cur[0]]["prefill_stream"]
+                if not st:                          # the whole device is reserved for decode
+                    held[0] += 1
+                    time.sleep(dt / 4)
+                    continue
+                load.prefill_loop(st)
+                torch.cuda.ExternalStream(st).synchronize()
+                loops[0] += 1
+
+        td, tp = threading.Thread(target=decode_thread), threading.Thread(target=prefill_thread)
+        t_start = time.perf_counter()
+        td.start()
+        tp.start()
+        traj, bind_us = [], []
+        n_int = args.ctl_intervals
+        for k in range(n_int):
+            if k == n_int // 2:
+                nsess[0] = max(1, load.dec.b.batch // 4)
+                n_heavy_steps = len(dec_lat)
+            time.sleep(dt)
+            st = ctl.tick()
+            t0 = time.perf_counter()
+            i = slots.bind(st["r_min"])
+            cur[0] = i
+            bind_us.append((time.perf_counter() - t0) * 1e6)
+            traj.append({"t_ms": (time.perf_counter() - t_start) * 1e3, "tpot_us": st["tpot_us"], "r_min": st["r_min"],
+                         "b_prefill": st["b_prefill"], "decode_units": entries[i]["decode_units"]})
+        stop.set()
+        td.join()
+        tp.join()
+        wall = time.perf_counter() - t_start
+        torch.cuda.synchronize()
+        def phase(tr, lats):
+            tail = tr[len(tr) // 2:]                 # second half of the phase: after the transient
+            ok = [x["tpot_us"] for x in tail if x["tpot_us"] == x["tpot_us"]]
+            units = tail[-1]["decode_units"]
+            steady = [us for (i, us) in lats[len(lats) // 2:] if entries[i]["decode_units"] == units]
+            return {"settled_decode_units": units, "levels_seen_after_transient": sorted({x["decode_units"] for x in tail}),
+                    "tpot_us_mean": float(np.mean(ok)) if ok else None,
+                    "step_p50_us": pct(steady, 50) if steady else None, "step_p99_us": pct(steady, 99) if steady else None,
+                    "intervals_to_settle": next((k for k in range(len(tr)) if all(x["decode_units"] == units for x in tr[k:])), None)}
+
+        heavy = phase(traj[:n_int // 2], dec_lat[:n_heavy_steps])
+        light = phase(traj[n_int // 2:], dec_lat[n_heavy_steps:])
+        res_lens = load.m.resume.new_lens
+        out.update({
+            "params": params, "interval_ms": args.ctl_interval_ms, "intervals": n_int,
+            "decode_alone_p50_us": alone,
+            "trajectory_r_min": [x["r_min"] for x in traj], "trajectory_b_prefill": [x["b_prefill"] for x in traj],
+            "trajectory_tpot_us": [None if x["tpot_us"] != x["tpot_us"] else round(x["tpot_us"], 1) for x in traj],
+            "phase_all_sessions": heavy, "phase_quarter_of_sessions": light,
+            "heavy_p99_over_alone_p50": heavy["step_p99_us"] / alone if heavy["step_p99_us"] else None,
+            "decode_steps": len(dec_lat) + len(dec_after_rebind),
+            "prefill_tokens_per_s": loops[0] * load.prefill_tokens / wall, "prefill_loops": loops[0],
+            "prefill_held_polls": held[0],
+            "rebinds": len(dec_after_rebind),
+            "rebind_host_us_mean": float(np.mean(bind_us)), "rebind_host_us_max": float(np.max(bind_us)),
+            "first_step_after_rebind_us_median": pct([u for _, u in dec_after_rebind], 50) if dec_after_rebind else None,
+            "epsilon_ctx_bound": float(np.max(bind_us)) / (args.ctl_interval_ms * 1e3),
+            "resume_chunks_admitted_to_decode_queue_at_end": int(sum(
+                ctl.classify(B.AG_REQ_RESUME, int(n)) == B.AG_QUEUE_DECODE for n in res_lens)),
+            "resume_chunks": int(len(res_lens)),
+        })
+        ctl.close()
+    finally:
+        sys.setswitchinterval(old_si)
+        torch.cuda.synchronize()
+        slots.close()
+    log("controller", json.dumps(out))
+    return out
+
+
 # --------------------------------------------------------------------------- CU-share profile (Fig. 3 analogue)
 def bench_cushare(args, torch, B, I, info):
     """Throughput of the three request classes alone on R CUs per XCD, R = 1..32: the MI355X analogue of the
@@ -446,6 +583,22 @@ def bench_cushare(args, torch, B, I, info):
     # TPOT budget tau_max (ms): r_min = 1000 / tau_max steps per second
     out["min_share_for_tpot_ms"] = {str(tau): next((r for r, v in zip(shares, out["decode_steps_per_s"]) if v >= 1000.0 / tau), None)
                                     for tau in (0.25, 0.5, 1.0, 2.0)}
+    # The paper's retention bound (Sec. III-B, Theorem 1) on the measured profiles, for the discrete allocation
+    # set G = {g, 2g, ..., S} with g = 4 units: R_g* = min{R in G : mu_D(R) >= 1000 / tau_max}, overshoot delta = g
+    # (one step of the allocation set), control overhead eps taken as 0 here (a rebinding is a table lookup, measured
+    # by the controller workload): rho >= mu_P(S - R_g* - delta) / mu_P(S - R_g*), for an all-cold (eta = 1) and an
+    # all-resume (eta = 0) prefill mix.
+    gset = [r for r in shares if r % 4 == 0]
+    mu = {k: dict(zip(shares, out[k])) for k in ("decode_steps_per_s", "cold_tokens_per_s", "resume_tokens_per_s")}
+    bound = {}
+    for tau in (0.2, 0.25, 0.3, 0.5, 1.0):
+        rg = next((r for r in gset if mu["decode_steps_per_s"][r] >= 1000.0 / tau), None)
+        e = {"R_g_star": rg}
+        if rg is not None and per - rg - 4 in mu["cold_tokens_per_s"] and per - rg in mu["cold_tokens_per_s"] and per - rg - 4 > 0:
+            e["rho_cold"] = mu["cold_tokens_per_s"][per - rg - 4] / mu["cold_tokens_per_s"][per - rg]
+            e["rho_resume"] = mu["resume_tokens_per_s"][per - rg - 4] / mu["resume_tokens_per_s"][per - rg]
+        bound[str(tau)] = e
+    out["theorem1_bound_for_tpot_ms"] = bound
     return out
 
 
@@ -471,6 +624,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=4, help="disjoint session sets the decode step rotates over")
     ap.add_argument("--mixed-steps", type=int, default=1000)
+    ap.add_argument("--ctl-interval-ms", type=float, default=20.0, help="control interval of the closed-loop workload")
+    ap.add_argument("--ctl-intervals", type=int, default=100)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only; run with --gpus 1 (the path shards by session or "
@@ -495,6 +650,8 @@ def main():
         res["resume_prefill"] = bench_prefill("resume", args, torch, B, I)
     if "mixed" in want:
         res["mixed"] = bench_mixed(args, torch, B, I, info)
+    if "controller" in want:
+        res["controller"] = bench_controller(args, torch, B, I, info)
     if "cushare" in want:
         res["cu_share_profile"] = bench_cushare(args, torch, B, I, info)
     if "copycal" in want:
