@@ -154,6 +154,25 @@ AG_API ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* o
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The decode queue's batch in one launch (paper Sec. III-A: short resume prefills are merged with decodes;
+ * Algorithm 1: a request joins Q_D if it is a decode or no longer than B_prefill).  Semantics are exactly
+ * ag_attn_resume's: session s brings new_lens[s] >= 0 query rows at positions prefix_lens[s] + i that attend
+ * causally to the session's keys; a decode is the case new_lens[s] = 1, prefix_lens[s] = ctx - 1.  What
+ * differs is the schedule: the keys of each session are split over workgroups as in ag_attn_decode, which
+ * pays when sessions bring few rows (the launch is then bound by reading K and V); for chunks of hundreds of
+ * rows ag_attn_resume is the faster call.  Arguments as ag_attn_resume, plus a device workspace of at least
+ * ag_attn_merged_workspace_bytes(total_new, num_q_heads, max_ctx) bytes, 16-byte aligned, which the call may
+ * overwrite entirely (AG_ERR_WORKSPACE if smaller).  Calls sharing a workspace must be ordered on one stream.
+ */
+AG_API size_t ag_attn_merged_workspace_bytes(int32_t total_new, int32_t num_q_heads, int32_t max_ctx);
+AG_API ag_status ag_attn_merged(const ag_kv_cache* cache, const void* q, void* out,
+                         const int32_t* block_tables, int32_t max_pages_per_seq,
+                         const int32_t* prefix_lens, const int32_t* new_lens, const int32_t* cu_new, /* device */
+                         int32_t batch, int32_t total_new, int32_t max_new, int32_t max_ctx,
+                         int32_t num_q_heads, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * CU-masked streams: the counterpart of the paper's pre-created SM partitions
  * (Sec. III-C; Algorithm 1 "partition SMs").  Kernels launched on the returned
  * stream run only on the compute units whose bit is set.  cu_mask_words is a

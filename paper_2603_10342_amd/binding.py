@@ -22,6 +22,7 @@ AG_F32, AG_BF16 = 0, 1
 
 EXPORTS = [
     "ag_kv_append", "ag_attn_prefill", "ag_attn_resume", "ag_attn_decode_workspace_bytes", "ag_attn_decode",
+    "ag_attn_merged_workspace_bytes", "ag_attn_merged",
     "ag_stream_create_cumask", "ag_stream_destroy", "ag_cumask_build", "ag_probe_placement", "ag_device_info",
     "ag_debug_validate", "ag_prof_enable", "ag_prof_collect", "ag_prof_disable", "ag_status_string",
     "ag_last_error", "ag_version",
@@ -78,6 +79,10 @@ def lib():
     l.ag_attn_decode_workspace_bytes.argtypes = [i32, i32, i32, i32]
     l.ag_attn_decode_workspace_bytes.restype = C.c_size_t
     l.ag_attn_decode.argtypes = [cp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp, C.c_size_t, vp]
+    l.ag_attn_merged_workspace_bytes.argtypes = [i32, i32, i32]
+    l.ag_attn_merged_workspace_bytes.restype = C.c_size_t
+    l.ag_attn_merged.argtypes = [cp, vp, vp, i32p, i32, i32p, i32p, i32p, i32, i32, i32, i32, i32, C.c_float, vp,
+                                 C.c_size_t, vp]
     l.ag_stream_create_cumask.argtypes = [C.POINTER(vp), u32p, i32]
     l.ag_stream_destroy.argtypes = [vp]
     l.ag_cumask_build.argtypes = [u32p, i32, i32, i32, i32, i32]
@@ -102,7 +107,7 @@ def lib():
     l.ag_slots_bind.argtypes = [vp, i32, C.POINTER(i32)]
     l.ag_slots_current.argtypes = [vp]
     for name in EXPORTS:
-        if name not in ("ag_attn_decode_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
+        if name not in ("ag_attn_decode_workspace_bytes", "ag_attn_merged_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
             getattr(l, name).restype = C.c_int
     l.ag_status_string.argtypes = [C.c_int]
     for name in ("ag_status_string", "ag_last_error", "ag_version"):
@@ -213,6 +218,19 @@ def ag_attn_decode(cache: KVCache, q, out, block_tables, ctx_lens, max_ctx: int,
     c = cache.c_struct()
     _check(lib().ag_attn_decode(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
                                 _i32(ctx_lens), ctx_lens.shape[0], max_ctx, num_q_heads, scale, _ptr(workspace),
+                                workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def ag_attn_merged_workspace_bytes(total_new: int, num_q_heads: int, max_ctx: int) -> int:
+    return int(lib().ag_attn_merged_workspace_bytes(total_new, num_q_heads, max_ctx))
+
+
+def ag_attn_merged(cache: KVCache, q, out, block_tables, prefix_lens, new_lens, cu_new, total_new: int,
+                   max_new: int, max_ctx: int, num_q_heads: int, scale: float, workspace: torch.Tensor, stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_attn_merged(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
+                                _i32(prefix_lens), _i32(new_lens), _i32(cu_new), new_lens.shape[0], total_new,
+                                max_new, max_ctx, num_q_heads, scale, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
 
 

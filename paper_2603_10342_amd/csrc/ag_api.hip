@@ -100,7 +100,8 @@ static ag_status check_scale(float scale)
 static ag_status prefill_common(const ag_kv_cache* cache, const void* q, void* out, const int32_t* bt, int max_pages,
                                 const int32_t* prefix_lens, bool need_prefix, const int32_t* new_lens,
                                 const int32_t* cu_new, int batch, int total_new, int max_new, int max_ctx, int hq,
-                                float scale, void* stream)
+                                float scale, void* stream, bool merged = false, void* workspace = nullptr,
+                                size_t workspace_bytes = 0)
 {
     CacheView c;
     ag_status st = view_cache(cache, &c);
@@ -121,12 +122,24 @@ static ag_status prefill_common(const ag_kv_cache* cache, const void* q, void* o
         set_error("max_ctx %d exceeds max_pages_per_seq * page_size = %lld", max_ctx, (long long)max_pages * c.ps);
         return AG_ERR_INVALID_ARG;
     }
+    if (merged) {
+        const size_t need = merged_workspace_bytes(total_new, hq, max_ctx);
+        if (workspace_bytes < need || (need && !workspace)) {
+            set_error("merged-batch workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+            return AG_ERR_WORKSPACE;
+        }
+        if (((uintptr_t)workspace) % 16) { set_error("merged-batch workspace must be 16-byte aligned"); return AG_ERR_INVALID_ARG; }
+    }
     if (total_new == 0 || max_new == 0) return AG_OK;
 
     AttnArgs a;
     a.q = q; a.out = out; a.c = c; a.bt = bt; a.max_pages = max_pages;
     a.prefix_lens = prefix_lens; a.new_lens = new_lens; a.cu_new = cu_new; a.ctx_lens = nullptr;
     a.batch = batch; a.total_rows = total_new; a.max_new = max_new; a.max_ctx = max_ctx; a.hq = hq; a.scale = scale;
+    if (merged) {
+        if (merged_mfma_supported(a)) return launch_merged_mfma(a, workspace, (hipStream_t)stream);
+        return launch_attn_general(a, (hipStream_t)stream);
+    }
     if (prefill_mfma_supported(a)) return launch_prefill_mfma(a, (hipStream_t)stream);
     return launch_attn_general(a, (hipStream_t)stream);
 }
@@ -176,6 +189,21 @@ ag_status ag_attn_resume(const ag_kv_cache* cache, const void* q, void* out, con
 {
     return prefill_common(cache, q, out, block_tables, max_pages_per_seq, prefix_lens, true, new_lens, cu_new, batch,
                           total_new, max_new, max_ctx, num_q_heads, scale, stream);
+}
+
+size_t ag_attn_merged_workspace_bytes(int32_t total_new, int32_t num_q_heads, int32_t max_ctx)
+{
+    if (total_new < 0 || num_q_heads <= 0 || max_ctx < 0) return 0;
+    return merged_workspace_bytes(total_new, num_q_heads, max_ctx);
+}
+
+ag_status ag_attn_merged(const ag_kv_cache* cache, const void* q, void* out, const int32_t* block_tables,
+                         int32_t max_pages_per_seq, const int32_t* prefix_lens, const int32_t* new_lens,
+                         const int32_t* cu_new, int32_t batch, int32_t total_new, int32_t max_new, int32_t max_ctx,
+                         int32_t num_q_heads, float scale, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return prefill_common(cache, q, out, block_tables, max_pages_per_seq, prefix_lens, true, new_lens, cu_new, batch,
+                          total_new, max_new, max_ctx, num_q_heads, scale, stream, true, workspace, workspace_bytes);
 }
 
 size_t ag_attn_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t max_ctx)

@@ -66,6 +66,11 @@ bool      decode_mfma_supported(const AttnArgs& a);
 size_t    decode_workspace_bytes(int batch, int hq, int d, int max_ctx);
 ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st);
 
+// merged decode + short-resume batch (same shapes as the decode path)
+bool      merged_mfma_supported(const AttnArgs& a);
+size_t    merged_workspace_bytes(int total_rows, int hq, int max_ctx);
+ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st);
+
 ag_status launch_probe(uint32_t* ids_out, int n_wg, int spin_cycles, hipStream_t st);
 
 }  // namespace ag

@@ -1,0 +1,54 @@
+// Pieces shared by the two split-K kernels over a paged KV cache (bf16, head_dim 128, page 16): the decode
+// step and the merged decode + short-resume batch.  Internal; nothing here is part of the ABI.
+#pragma once
+
+#include "ag_internal.h"
+
+namespace ag {
+namespace splitk {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int D = 128;
+constexpr int PS = 16;
+#ifndef AG_DECODE_PREFETCH
+#define AG_DECODE_PREFETCH 0
+#endif
+
+// Tokens of one part of a session's context when it is cut for splits of at most `split` tokens:
+// n = ceil(ctx / split) equal parts, each a multiple of 128 (32 per wave step x 4 waves).
+__host__ __device__ inline int part_tokens(int ctx, int split)
+{
+    const int n = (ctx + split - 1) / split;
+    return (((ctx + n - 1) / n) + 127) & ~127;
+}
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ __forceinline__ bf16x8 ld16(const __bf16* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// v holds 8 tokens: elements 0..3 are tokens j = 0..3, elements 4..7 tokens j = 8..11 of the lane's run.
+// Zero element e < 4 unless e < keep_lo, and element 4 + e unless e < keep_hi.
+__device__ __forceinline__ bf16x8 keep_quads(bf16x8 v, int keep_lo, int keep_hi)
+{
+    u32x4 u = __builtin_bit_cast(u32x4, v);
+#pragma unroll
+    for (int w = 0; w < 2; ++w) {
+        u[w] &= ((2 * w < keep_lo) ? 0x0000FFFFu : 0u) | ((2 * w + 1 < keep_lo) ? 0xFFFF0000u : 0u);
+        u[2 + w] &= ((2 * w < keep_hi) ? 0x0000FFFFu : 0u) | ((2 * w + 1 < keep_hi) ? 0xFFFF0000u : 0u);
+    }
+    return __builtin_bit_cast(bf16x8, u);
+}
+
+struct StepRegs {       // one wave's K and V operands for 32 tokens (two pages)
+    bf16x8 k1[4], k2[4], v[8];
+};
+
+
+// Workspace is sized for the smallest split a launcher may choose.
+constexpr int kMinSplit = 256;
+inline int splits_for(int max_ctx, int split) { return max_ctx <= 0 ? 1 : (max_ctx + split - 1) / split; }
+
+}  // namespace splitk
+}  // namespace ag

@@ -132,3 +132,12 @@ def run_phase(cache, kp, vp, b: I.Batch, kind: str, scale=None):
     else:
         got = gpu_decode(cache, d.q, d.bt, d.ctx, d.max_ctx, d.geom, scale)
     return got, ref
+
+
+def gpu_merged(cache, d: DevBatch, scale=None):
+    nbytes = B.ag_attn_merged_workspace_bytes(d.total, d.geom.num_q_heads, d.max_ctx)
+    ws = torch.full((max(nbytes, 16) // 4,), float("nan"), dtype=torch.float32, device=DEV)
+    B.ag_attn_merged(cache, d.q, d.out, d.bt, d.prefix, d.new, d.cu, d.total, d.max_new, d.max_ctx,
+                     d.geom.num_q_heads, d.geom.scale if scale is None else scale, ws)
+    torch.cuda.synchronize()
+    return to_f64(d.out, d.geom.dtype)
