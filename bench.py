@@ -398,6 +398,72 @@ def bench_mixed(args, torch, B, I, info):
     return out
 
 
+# --------------------------------------------------------------------------- decode queue in one launch
+def bench_merged(args, torch, B, I):
+    """The decode queue of a scheduling step (64 decodes + 8 short resume chunks) three ways: one merged launch
+    (ag_attn_merged), the decode and resume entry points one after the other, and the resume entry point on
+    everything."""
+    lo, hi = (int(x) for x in args.merged_rows.split(","))
+    c = I.make_decode_queue(n_lo=lo, n_hi=hi)
+    g = c.geom
+    fill, ch = Dev(c.fill, torch), Dev(c.chunk, torch)
+    cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+    B.ag_kv_append(cache, fill.k_new, fill.v_new, fill.bt, fill.prefix, fill.new, fill.cu, fill.total)
+    B.ag_kv_append(cache, ch.k_new, ch.v_new, ch.bt, ch.prefix, ch.new, ch.cu, ch.total)
+    nd = int((c.chunk.new_lens == 1).sum())                # the decodes come first
+    ws = torch.empty(B.ag_attn_merged_workspace_bytes(ch.total, g.num_q_heads, ch.max_ctx) // 4, dtype=torch.float32, device="cuda")
+    wsd = torch.empty(B.ag_attn_decode_workspace_bytes(nd, g.num_q_heads, g.head_dim, ch.max_ctx) // 4, dtype=torch.float32, device="cuda")
+    cu_r = (ch.cu[nd:] - nd).contiguous()
+    max_new_r = int(c.chunk.new_lens[nd:].max())
+    out_m, out_s, out_r = (torch.zeros_like(ch.q) for _ in range(3))
+    torch.cuda.synchronize()
+
+    def merged(i):
+        B.ag_attn_merged(cache, ch.q, out_m, ch.bt, ch.prefix, ch.new, ch.cu, ch.total, ch.max_new, ch.max_ctx,
+                         g.num_q_heads, g.scale, ws)
+
+    def separate(i):
+        B.ag_attn_decode(cache, ch.q[:nd], out_s[:nd], ch.bt[:nd], ch.ctx[:nd], ch.max_ctx, g.num_q_heads, g.scale, wsd)
+        B.ag_attn_resume(cache, ch.q[nd:], out_s[nd:], ch.bt[nd:], ch.prefix[nd:], ch.new[nd:], cu_r, ch.total - nd,
+                         max_new_r, ch.max_ctx, g.num_q_heads, g.scale)
+
+    def resume_all(i):
+        B.ag_attn_resume(cache, ch.q, out_r, ch.bt, ch.prefix, ch.new, ch.cu, ch.total, ch.max_new, ch.max_ctx,
+                         g.num_q_heads, g.scale)
+
+    steps, warmup = args.steps, args.warmup
+    t_m = time_steps(torch, merged, steps, warmup)
+    prof = kernel_time(B, torch, merged, steps, warmup)
+    t_s = time_steps(torch, separate, steps, warmup)
+    t_r = time_steps(torch, resume_all, max(5, steps // 4), 2)
+    ctx = c.chunk.ctx_lens.astype(np.int64)
+    kv_bytes = int(ctx.sum()) * g.kv_bytes_per_token
+    qo_bytes = 2 * ch.total * g.num_q_heads * g.head_dim * 2
+    out = {
+        "sessions_decoding": nd, "sessions_resuming": int(len(ctx) - nd), "rows": ch.total,
+        "resume_rows": [int(x) for x in c.chunk.new_lens[nd:]],
+        "merged_us": t_m * 1e6, "decode_then_resume_us": t_s * 1e6, "resume_entry_point_on_all_us": t_r * 1e6,
+        "merged_split_kernel_us": prof["mean_us"],
+        "kv_bytes_once": kv_bytes, "merged_GBps_of_kv_once": (kv_bytes + qo_bytes) / t_m / 1e9,
+        "flops": c.chunk.attn_flops(),
+        "max_abs_merged_vs_separate": float((out_m.float() - out_s.float()).abs().max()),
+        "max_abs_merged_vs_resume_all": float((out_m.float() - out_r.float()).abs().max()),
+    }
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O       # check leg
+        kp, vp = I.zero_pool(g.pool_shape, g.dtype), I.zero_pool(g.pool_shape, g.dtype)
+        for b in (c.fill, c.chunk):
+            O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
+        b = c.chunk
+        ref = O.attn(kp, vp, g.dtype, b.q, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new, g.num_q_heads, g.scale)
+        got = I.stored_to_f64(out_m.view(torch.int16).cpu().numpy().view(np.uint16), g.dtype)
+        err = np.abs(got - ref)
+        out["check_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                                  "rel_fro": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
+    log("merged", json.dumps(out))
+    return out
+
+
 # --------------------------------------------------------------------------- closed loop (Algorithm 1)
 def bench_controller(args, torch, B, I, info):
     """Config 5's load under the TPOT-driven controller (paper Sec. III-B, Algorithm 1) and the table of
@@ -624,6 +690,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=4, help="disjoint session sets the decode step rotates over")
     ap.add_argument("--mixed-steps", type=int, default=1000)
+    ap.add_argument("--merged-rows", default="16,64", help="range of the resume chunks' rows in the merged workload")
     ap.add_argument("--ctl-interval-ms", type=float, default=20.0, help="control interval of the closed-loop workload")
     ap.add_argument("--ctl-intervals", type=int, default=100)
     args = ap.parse_args()
@@ -650,6 +717,8 @@ def main():
         res["resume_prefill"] = bench_prefill("resume", args, torch, B, I)
     if "mixed" in want:
         res["mixed"] = bench_mixed(args, torch, B, I, info)
+    if "merged" in want:
+        res["decode_queue_merged"] = bench_merged(args, torch, B, I)
     if "controller" in want:
         res["controller"] = bench_controller(args, torch, B, I, info)
     if "cushare" in want:

@@ -6,15 +6,16 @@
 // to the session's keys: the semantics of the resume prefill.  The work is cut the way the decode step cuts
 // it, because with few query rows per session the kernel is bound by reading K and V, not by arithmetic:
 //
-//   plan kernel     lists the items: an item is up to tq = 16 / G consecutive rows of one session (G = query
-//                   heads per KV head), so that its tq x G (row, head) pairs fill the 16 columns of the matrix
-//                   instruction that the decode step leaves mostly empty; also notes each row's session.
+//   plan kernel     lists the items: an item is up to R groups of tq = 16 / G consecutive rows of one session
+//                   (G = query heads per KV head), so that a group's tq x G (row, head) pairs fill the 16
+//                   columns of the matrix instruction that the decode step leaves mostly empty; also notes
+//                   each row's session.
 //   split kernel    one workgroup per (item, KV head, split of the keys the item's last row may see); the
 //                   decode step's loop, with a visibility limit per column instead of per session.
 //   merge kernel    one workgroup per (row, head) combines the splits in split order.
 //
 // K and V of a session are fetched by each of its items; items of one (session, KV head, split) are dealt to
-// the same XCD (their linear workgroup ids differ by a multiple of 8 when splits * KV heads is one), so the
+// the same XCD (their linear workgroup ids differ by a multiple of 8 when splits * KV heads is one such), so the
 // repeats are served by that XCD's L2.
 #include <algorithm>
 
@@ -26,7 +27,7 @@ namespace {
 
 using namespace splitk;
 
-// plan[0] = number of items, plan[2 + 2i] = session, plan[3 + 2i] = first row / tq of item i;
+// plan[0] = number of items, plan[2 + 2i] = session, plan[3 + 2i] = (first row of item i) / (rows per item, `tq` here);
 // row_sess[row] = session of query row `row`.  Block 0 lists the items, the other blocks the rows.
 __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restrict__ new_lens,
                                                           const int32_t* __restrict__ cu_new, int batch,
@@ -72,23 +73,28 @@ __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restr
 }
 
 // kSteps: steps of 32 keys a wave may walk; the split size is 128 * kSteps keys.
-template <int kSteps>
-__global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, float* __restrict__ ws_o,
-                                                              float* __restrict__ ws_ml,
-                                                              const int32_t* __restrict__ plan, int n_splits_max, int tq)
+// R: column groups per item.  An item is R * tq rows; each K / V step is loaded once and used by the R groups
+// one after the other, which divides the number of times a session's keys are fetched by R at the price of
+// R times the accumulators (fewer waves per SIMD).
+template <int kSteps, int R>
+__global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnArgs a, float* __restrict__ ws_o,
+                                                                           float* __restrict__ ws_ml,
+                                                                           const int32_t* __restrict__ plan,
+                                                                           int n_splits_max, int tq)
 {
     constexpr int kSplit = 128 * kSteps;
-    __shared__ float s_o[4][16][D];     // per wave, per column: unnormalised O
+    __shared__ float s_o[4][16][D];     // per wave, per column of one group: unnormalised O
     __shared__ float s_m[4][16];
     __shared__ float s_l[4][16];
 
     const int split = blockIdx.x, g = blockIdx.y, item = blockIdx.z;
     if (item >= plan[0]) return;
+    const int rows_item = R * tq;
     const int s = plan[2 + 2 * item];
-    const int t0 = plan[3 + 2 * item] * tq;          // first row of the item within the session's chunk
+    const int t0 = plan[3 + 2 * item] * rows_item;   // first row of the item within the session's chunk
     const int N = a.new_lens[s];
     const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
-    const int nt = min(tq, N - t0);                  // rows of this item, >= 1
+    const int nt = min(rows_item, N - t0);           // rows of this item, >= 1
     const int ctx_all = P + N;                       // slots below this hold tokens
     const int ctx = P + t0 + nt;                     // keys the item's last row may see
     const int part = part_tokens(ctx, kSplit);
@@ -105,19 +111,23 @@ __global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, float*
     const __bf16* kpool = (const __bf16*)a.c.k;
     const __bf16* vpool = (const __bf16*)a.c.v;
 
-    // column r = (row r / G of the item, head r % G of the group); columns without a row carry a zero query
+    // column r of group j = (row j * tq + r / G of the item, head r % G of the KV head's group); columns
+    // without a row carry a zero query and the visibility of the item's last row
     const int col_row = r / G, col_head = r - col_row * G;
-    const bool col_on = col_row < nt;
-    const int pos = P + t0 + (col_on ? col_row : nt - 1);       // last key the column may see
-    const int64_t q_row = (int64_t)a.cu_new[s] + t0 + (col_on ? col_row : 0);
-    bf16x8 qf[4];
-    {
+    int pos[R];
+    bf16x8 qf[R][4];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int row = j * tq + col_row;
+        const bool on = col_row < tq && row < nt;
+        pos[j] = P + t0 + (on ? row : nt - 1);
+        const int64_t q_row = (int64_t)a.cu_new[s] + t0 + (on ? row : 0);
         const __bf16* qrow = (const __bf16*)a.q + (q_row * hq + (int64_t)g * G + col_head) * D + c * 8;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             bf16x8 x = ld16(qrow + kk * 32);
-            if (!col_on) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            qf[kk] = x;
+            if (!on) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            qf[j][kk] = x;
         }
     }
 
@@ -130,10 +140,15 @@ __global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, float*
     const int n_steps = wstart < ctx ? min(wave_tok >> 5, (ctx - wstart + 31) >> 5) : 0;   // uniform over the wave
 
     const float sl2 = a.scale * kLog2e;
-    float m = -INFINITY, lsum = 0.0f;
-    f32x4 o[8];
+    float m[R], lsum[R];
+    f32x4 o[R][8];
 #pragma unroll
-    for (int mb = 0; mb < 8; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < R; ++j) {
+        m[j] = -INFINITY;
+        lsum[j] = 0.0f;
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb) o[j][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
 
     // operand addressing as in the decode step: score row r is slot (r & 7) of page (r >> 3) of the step, the
     // second score product takes slots 8..15; lane group c owns the 8 keys of value chunk (c & 1) of page (c >> 1)
@@ -160,84 +175,94 @@ __global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, float*
                 for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16(vp + mb * 16 * 8);
             }
             const int tok0 = wstart + st * 32;
-            f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qf[kk], s1, 0, 0, 0);
-                s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qf[kk], s2, 0, 0, 0);
-            }
-            // s1[i]: key tokb + i, s2[i]: key tokb + 8 + i, of column r
             const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
-            const int keep = pos + 1 - tokb;         // key tokb + j is visible to this column iff j < keep
-            float xs[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
-                xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
-            }
-            float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16));
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float m_new = fmaxf(m, mx);
-            // a column may see none of this wave's keys so far (its row lies before them): keep the exponents finite
-            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
-            float psum = 0.f;
-            bf16x8 pb;
+            for (int j = 0; j < R; ++j) {
+                f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
-                psum += p;
-                pb[e] = (__bf16)p;
-            }
-            lsum = lsum * alpha + psum;
-            m = m_new;
-            if (tok0 + 32 > ctx_all) {       // slots past the session's last token may hold anything, NaN included
-                const int keep_v = ctx_all - tokb;
+                for (int kk = 0; kk < 4; ++kk) {
+                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qf[j][kk], s1, 0, 0, 0);
+                    s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qf[j][kk], s2, 0, 0, 0);
+                }
+                // s1[i]: key tokb + i, s2[i]: key tokb + 8 + i, of column r
+                const int keep = pos[j] + 1 - tokb;  // key tokb + i is visible to this column iff i < keep
+                float xs[8];
 #pragma unroll
-                for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep_v, keep_v - 8);
-            }
+                for (int i = 0; i < 4; ++i) {
+                    xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
+                    xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
+                }
+                float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m[j], mx);
+                // a column may see none of this wave's keys so far (its row lies before them): keep the exponents finite
+                const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+                const float alpha = __builtin_amdgcn_exp2f(m[j] - m_ref);
+                float psum = 0.f;
+                bf16x8 pb;
 #pragma unroll
-            for (int mb = 0; mb < 8; ++mb) {
-                o[mb] *= alpha;
-                o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[mb], 0, 0, 0);
+                for (int e = 0; e < 8; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
+                    psum += p;
+                    pb[e] = (__bf16)p;
+                }
+                lsum[j] = lsum[j] * alpha + psum;
+                m[j] = m_new;
+                if (j == 0 && tok0 + 32 > ctx_all) {   // slots past the session's last token may hold anything, NaN included
+                    const int keep_v = ctx_all - tokb;
+#pragma unroll
+                    for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep_v, keep_v - 8);
+                }
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) {
+                    o[j][mb] *= alpha;
+                    o[j][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[j][mb], 0, 0, 0);
+                }
             }
         }
     }
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
 
-    // o[mb][i] is O^T[d = mb*16 + c*4 + i][column r]
+    // the four waves' partials of one group at a time through LDS
 #pragma unroll
-    for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(&s_o[w][r][mb * 16 + c * 4]) = o[mb];
-    if (c == 0) { s_m[w][r] = m; s_l[w][r] = lsum; }
-    __syncthreads();
-
-    const int n_cols = nt * G;
-    for (int idx = threadIdx.x; idx < n_cols * D; idx += 256) {
-        const int col = idx >> 7, d = idx & (D - 1);
-        float ms = s_m[0][col];
+    for (int j = 0; j < R; ++j) {
+        const int rows_here = min(tq, nt - j * tq);          // rows of group j; uniform over the workgroup
+        if (rows_here <= 0) break;
+        float l = lsum[j];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (j > 0) __syncthreads();                          // the previous group's readers are done
+        // o[j][mb][i] is O^T[d = mb*16 + c*4 + i][column r]
 #pragma unroll
-        for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][col]);
-        float acc = 0.f, l = 0.f;
+        for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(&s_o[w][r][mb * 16 + c * 4]) = o[j][mb];
+        if (c == 0) { s_m[w][r] = m[j]; s_l[w][r] = l; }
+        __syncthreads();
+        const int n_cols = rows_here * G;
+        for (int idx = threadIdx.x; idx < n_cols * D; idx += 256) {
+            const int col = idx >> 7, d = idx & (D - 1);
+            float ms = s_m[0][col];
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) {
-            const float mw = s_m[ww][col];
-            const float f = mw == -INFINITY ? 0.f : exp2f(mw - ms);    // a wave that saw no key of this column
-            acc += f * s_o[ww][col][d];
-            l += f * s_l[ww][col];
+            for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][col]);
+            float acc = 0.f, lt = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < 4; ++ww) {
+                const float mw = s_m[ww][col];
+                const float f = mw == -INFINITY ? 0.f : exp2f(mw - ms);    // a wave that saw no key of this column
+                acc += f * s_o[ww][col][d];
+                lt += f * s_l[ww][col];
+            }
+            const int crow = col / G, chead = col - crow * G;
+            const int64_t slot = (((int64_t)a.cu_new[s] + t0 + j * tq + crow) * hq + (int64_t)g * G + chead) * n_splits_max + split;
+            ws_o[slot * D + d] = acc;
+            if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = lt; }
         }
-        const int crow = col / G, chead = col - crow * G;
-        const int64_t slot = (((int64_t)a.cu_new[s] + t0 + crow) * hq + (int64_t)g * G + chead) * n_splits_max + split;
-        ws_o[slot * D + d] = acc;
-        if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = l; }
     }
 }
 
 __global__ __launch_bounds__(128) void merged_merge_kernel(AttnArgs a, const float* __restrict__ ws_o,
                                                            const float* __restrict__ ws_ml,
                                                            const int32_t* __restrict__ row_sess, int n_splits_max,
-                                                           int split_tokens, int tq)
+                                                           int split_tokens, int rows_item)
 {
     const int64_t rh = blockIdx.x;                 // row * hq + head
     const int row = (int)(rh / a.hq);
@@ -246,8 +271,8 @@ __global__ __launch_bounds__(128) void merged_merge_kernel(AttnArgs a, const flo
     const int t = row - a.cu_new[s];
     const int N = a.new_lens[s];
     const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
-    const int t0 = (t / tq) * tq;
-    const int ctx = P + t0 + min(tq, N - t0);      // as the split kernel cut the row's item
+    const int t0 = (t / rows_item) * rows_item;
+    const int ctx = P + t0 + min(rows_item, N - t0);      // as the split kernel cut the row's item
     const int part = part_tokens(ctx, split_tokens);
     const int n = (ctx + part - 1) / part;
     const int64_t base = rh * n_splits_max;
@@ -296,12 +321,32 @@ bool merged_mfma_supported(const AttnArgs& a)
            (((uintptr_t)a.q | (uintptr_t)a.c.k | (uintptr_t)a.c.v) % 16 == 0);
 }
 
+template <int R>
+static void launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml,
+                         const int32_t* plan, int nsm, int tq)
+{
+    switch (split) {
+        case 2048: hipLaunchKernelGGL((merged_split_kernel<16, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+        case 1024: hipLaunchKernelGGL((merged_split_kernel<8, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+        case 512:  hipLaunchKernelGGL((merged_split_kernel<4, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+        default:   hipLaunchKernelGGL((merged_split_kernel<2, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+    }
+}
+
 ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
     if (a.total_rows <= 0) return AG_OK;
     const int tq = rows_per_item(a.hq, a.c.hkv);
-    // every item has at least one row, and a session of N rows has ceil(N / tq) items
-    const int64_t items_max = std::min<int64_t>(a.total_rows, ((int64_t)a.total_rows + (int64_t)a.batch * (tq - 1)) / tq);
+    // Two column groups per item as soon as some session may bring more rows than one group holds: its keys
+    // are then fetched half as often.  A batch of decodes only keeps one group (and twice the waves per SIMD).
+#ifdef AG_MERGED_FORCE_R
+    const int R = AG_MERGED_FORCE_R;
+#else
+    const int R = a.max_new > tq ? 2 : 1;
+#endif
+    const int rows_item = R * tq;
+    // every item has at least one row, and a session of N rows has ceil(N / rows_item) items
+    const int64_t items_max = std::min<int64_t>(a.total_rows, ((int64_t)a.total_rows + (int64_t)a.batch * (rows_item - 1)) / rows_item);
     if (items_max > 65535 || a.c.hkv > 65535) { set_error("too many items (%lld) or KV heads for one launch grid", (long long)items_max); return AG_ERR_INVALID_ARG; }
     const int split = choose_split((int)items_max, a.c.hkv, a.max_ctx);
     const int nsm = splits_for(a.max_ctx, split);
@@ -312,21 +357,17 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     int32_t* row_sess = plan + L.plan_ints;
 
     hipLaunchKernelGGL(merged_plan_kernel, dim3(1 + (a.total_rows + 255) / 256), dim3(256), 0, st, a.new_lens, a.cu_new,
-                       a.batch, a.total_rows, tq, plan, row_sess);
+                       a.batch, a.total_rows, rows_item, plan, row_sess);
     ag_status e = hip_check(hipGetLastError(), "merged plan launch");
     if (e) return e;
     const dim3 grid(nsm, a.c.hkv, (unsigned)items_max);
     prof_before(st);
-    switch (split) {
-        case 2048: hipLaunchKernelGGL(merged_split_kernel<16>, grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        case 1024: hipLaunchKernelGGL(merged_split_kernel<8>, grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        case 512:  hipLaunchKernelGGL(merged_split_kernel<4>, grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        default:   hipLaunchKernelGGL(merged_split_kernel<2>, grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-    }
+    if (R == 2) launch_split<2>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    else launch_split<1>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
     prof_after(st);
     if ((e = hip_check(hipGetLastError(), "merged split launch"))) return e;
     hipLaunchKernelGGL(merged_merge_kernel, dim3((unsigned)((int64_t)a.total_rows * a.hq)), dim3(128), 0, st, a, ws_o, ws_ml,
-                       row_sess, nsm, split, tq);
+                       row_sess, nsm, split, rows_item);
     return hip_check(hipGetLastError(), "merged merge launch");
 }
 

@@ -322,6 +322,25 @@ def make_decode(batch: int = 64, lo: int = 1024, hi: int = 4096, num_pages: int 
     return DecodeConfig(geom, bt, ctx, fill, step)
 
 
+def make_decode_queue(n_decode: int = 64, n_resume: int = 8, ctx_lo: int = 1024, ctx_hi: int = 4096,
+                      p_lo: int = 2048, p_hi: int = 8192, n_lo: int = 16, n_hi: int = 64, num_pages: int = 32768,
+                      seed: Optional[int] = None, sigma_qk: Optional[float] = None, sigma_v: Optional[float] = None,
+                      geom: Optional[Geometry] = None) -> "ResumeConfig":
+    """The decode queue of one scheduling step: n_decode sessions that decode (one row each, contexts as in
+    config 2) followed by n_resume sessions whose short tool output (n_lo..n_hi rows, prefixes as in config 4)
+    was admitted beside them.  `fill` builds the caches, `chunk` is the batch of the step."""
+    seed = config_seed(6) if seed is None else seed
+    geom = slm_geometry(num_pages) if geom is None else geom
+    rng = rng_for(seed, 0)
+    p = np.concatenate([uniform_lens(rng, ctx_lo, ctx_hi, n_decode) - 1, uniform_lens(rng, p_lo, p_hi, n_resume)]).astype(np.int32)
+    n = np.concatenate([np.ones(n_decode, np.int32), uniform_lens(rng, n_lo, n_hi, n_resume)]).astype(np.int32)
+    bt = deal_block_tables(rng, p + n, geom.page_size, geom.num_pages)
+    kw = dict(sigma_qk=sigma_qk, sigma_v=sigma_v)
+    fill = draw_batch(geom, bt, np.zeros(len(p), np.int32), p, seed + 50, 1, **kw)
+    chunk = draw_batch(geom, bt, p, n, seed + 50, 2, **kw)
+    return ResumeConfig(geom, bt, fill, chunk)
+
+
 def make_cold(batch: int = 8, n: int = 4096, num_pages: Optional[int] = None,
               seed: Optional[int] = None, sigma_qk: Optional[float] = None,
               sigma_v: Optional[float] = None, geom: Optional[Geometry] = None) -> Batch:
