@@ -72,7 +72,8 @@ typedef enum {
     AG_ERR_INVALID_ARG = -1,   /* null pointer, negative size, contradictory bounds */
     AG_ERR_UNSUPPORTED = -2,   /* dtype / head_dim / page_size outside the supported set */
     AG_ERR_WORKSPACE = -3,     /* decode workspace smaller than ag_attn_decode_workspace_bytes() */
-    AG_ERR_HIP = -4            /* a HIP runtime call failed; text in ag_last_error() */
+    AG_ERR_HIP = -4,           /* a HIP runtime call failed; text in ag_last_error() */
+    AG_ERR_NO_SPACE = -5       /* page manager (ag_pager.h): not enough free pages, sessions or row capacity */
 } ag_status;
 
 typedef enum { AG_F32 = 0, AG_BF16 = 1 } ag_dtype;

@@ -17,7 +17,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 # AGATTN_LIB selects another build of the same library (kernel tuning experiments); default is the in-tree build.
 LIB_PATH = os.environ.get("AGATTN_LIB") or os.path.join(HERE, "libagattn.so")
 
-AG_OK, AG_ERR_INVALID_ARG, AG_ERR_UNSUPPORTED, AG_ERR_WORKSPACE, AG_ERR_HIP = 0, -1, -2, -3, -4
+AG_OK, AG_ERR_INVALID_ARG, AG_ERR_UNSUPPORTED, AG_ERR_WORKSPACE, AG_ERR_HIP, AG_ERR_NO_SPACE = 0, -1, -2, -3, -4, -5
 AG_F32, AG_BF16 = 0, 1
 
 EXPORTS = [
@@ -30,7 +30,12 @@ EXPORTS = [
     "ag_ctl_create", "ag_ctl_destroy", "ag_ctl_record_decode", "ag_ctl_tick", "ag_ctl_get", "ag_ctl_classify",
     "ag_partition_level_for", "ag_slots_create", "ag_slots_destroy", "ag_slots_count", "ag_slots_units",
     "ag_slots_get", "ag_slots_bind", "ag_slots_current",
+    # ag_pager.h
+    "ag_pager_create", "ag_pager_destroy", "ag_pager_open", "ag_pager_close", "ag_pager_reserve", "ag_pager_seal",
+    "ag_pager_commit", "ag_pager_acquire", "ag_pager_lengths", "ag_pager_export", "ag_pager_page_state",
+    "ag_pager_get_stats",
 ]
+AG_PAGE_FREE, AG_PAGE_WRITABLE, AG_PAGE_SEALED = 0, 1, 2
 
 AG_REQ_DECODE, AG_REQ_RESUME, AG_REQ_COLD = 0, 1, 2
 AG_QUEUE_DECODE, AG_QUEUE_PREFILL = 0, 1
@@ -51,6 +56,12 @@ class ag_ctl_params(C.Structure):
 class ag_ctl_state(C.Structure):
     _fields_ = [("r_min", C.c_int32), ("b_prefill", C.c_int32), ("tpot_us", C.c_double),
                 ("intervals", C.c_int64), ("raised", C.c_int64), ("lowered", C.c_int64)]
+
+
+class ag_pager_stats(C.Structure):
+    _fields_ = [("num_pages", C.c_int32), ("free_pages", C.c_int32), ("open_sessions", C.c_int32),
+                ("reserves", C.c_int64), ("failed_reserves", C.c_int64), ("commits", C.c_int64),
+                ("waits_issued", C.c_int64), ("waits_skipped", C.c_int64)]
 
 
 class ag_kv_cache(C.Structure):
@@ -106,6 +117,19 @@ def lib():
     l.ag_slots_get.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(vp), C.POINTER(vp)]
     l.ag_slots_bind.argtypes = [vp, i32, C.POINTER(i32)]
     l.ag_slots_current.argtypes = [vp]
+    pi32 = C.POINTER(i32)
+    l.ag_pager_create.argtypes = [i32, i32, i32, i32, C.POINTER(vp)]
+    l.ag_pager_destroy.argtypes = [vp]
+    l.ag_pager_open.argtypes = [vp, pi32]
+    l.ag_pager_close.argtypes = [vp, i32]
+    l.ag_pager_reserve.argtypes = [vp, i32, i32, pi32]
+    l.ag_pager_seal.argtypes = [vp, i32]
+    l.ag_pager_commit.argtypes = [vp, i32, vp]
+    l.ag_pager_acquire.argtypes = [vp, i32, vp, pi32]
+    l.ag_pager_lengths.argtypes = [vp, i32, pi32, pi32, pi32]
+    l.ag_pager_export.argtypes = [vp, pi32, i32, pi32]
+    l.ag_pager_page_state.argtypes = [vp, i32]
+    l.ag_pager_get_stats.argtypes = [vp, C.POINTER(ag_pager_stats)]
     for name in EXPORTS:
         if name not in ("ag_attn_decode_workspace_bytes", "ag_attn_merged_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
             getattr(l, name).restype = C.c_int
@@ -380,3 +404,72 @@ class Slots:
 
     def current(self) -> int:
         return _nonneg(lib().ag_slots_current(self._h))
+
+
+# ---- ag_pager.h: KV page manager ----
+
+class Pager:
+    """Owns an ag_pager.  Methods are the entry points of the same name without the prefix."""
+
+    def __init__(self, num_pages: int, page_size: int, max_sessions: int, max_pages_per_seq: int):
+        h = C.c_void_p()
+        _check(lib().ag_pager_create(num_pages, page_size, max_sessions, max_pages_per_seq, C.byref(h)))
+        self._h = h
+        self.max_pages_per_seq = max_pages_per_seq
+
+    def destroy(self):
+        if self._h:
+            _check(lib().ag_pager_destroy(self._h))
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def open(self) -> int:
+        s = C.c_int32()
+        _check(lib().ag_pager_open(self._h, C.byref(s)))
+        return s.value
+
+    def close(self, session: int):
+        _check(lib().ag_pager_close(self._h, session))
+
+    def reserve(self, session: int, new_tokens: int) -> int:
+        start = C.c_int32()
+        _check(lib().ag_pager_reserve(self._h, session, new_tokens, C.byref(start)))
+        return start.value
+
+    def seal(self, session: int):
+        _check(lib().ag_pager_seal(self._h, session))
+
+    def commit(self, session: int, stream=None):
+        _check(lib().ag_pager_commit(self._h, session, _stream(stream)))
+
+    def acquire(self, session: int, stream=None) -> int:
+        n = C.c_int32()
+        _check(lib().ag_pager_acquire(self._h, session, _stream(stream), C.byref(n)))
+        return n.value
+
+    def lengths(self, session: int) -> dict:
+        r, s, p = C.c_int32(), C.c_int32(), C.c_int32()
+        _check(lib().ag_pager_lengths(self._h, session, C.byref(r), C.byref(s), C.byref(p)))
+        return {"reserved": r.value, "sealed": s.value, "pages": p.value}
+
+    def export(self, sessions: Sequence[int]):
+        """Block-table rows of the sessions as a host int32 array [n][max_pages_per_seq]."""
+        import numpy as np
+        n = len(sessions)
+        ids = (C.c_int32 * n)(*sessions)
+        rows = np.zeros((n, self.max_pages_per_seq), np.int32)
+        _check(lib().ag_pager_export(self._h, ids, n, rows.ctypes.data_as(C.POINTER(C.c_int32))))
+        return rows
+
+    def page_state(self, page: int) -> int:
+        return _nonneg(lib().ag_pager_page_state(self._h, page))
+
+    def stats(self) -> dict:
+        st = ag_pager_stats()
+        _check(lib().ag_pager_get_stats(self._h, C.byref(st)))
+        return {k: getattr(st, k) for k, _ in ag_pager_stats._fields_}

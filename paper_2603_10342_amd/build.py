@@ -12,7 +12,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libagattn.so")
 SOURCES = ["ag_api.hip", "kv_append.hip", "attn_general.hip", "attn_decode_mfma.hip", "attn_prefill_mfma.hip", "attn_merged_mfma.hip",
-           "ag_sched.hip"]
+           "ag_sched.hip", "ag_pager.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-strict-aliasing", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",      # no packed-fp32 instructions

@@ -410,6 +410,7 @@ const char* ag_status_string(ag_status s)
         case AG_ERR_UNSUPPORTED: return "AG_ERR_UNSUPPORTED";
         case AG_ERR_WORKSPACE: return "AG_ERR_WORKSPACE";
         case AG_ERR_HIP: return "AG_ERR_HIP";
+        case AG_ERR_NO_SPACE: return "AG_ERR_NO_SPACE";
     }
     return "AG_ERR_UNKNOWN";
 }
