@@ -242,7 +242,7 @@ def bench_prefill(kind, args, torch, B, I):
         kp, vp = I.zero_pool(g.pool_shape, g.dtype), I.zero_pool(g.pool_shape, g.dtype)
         O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
         rng = I.rng_for(I.config_seed(3), 77)
-        n_rows = 256
+        n_rows = 8192
         rs = rng.integers(0, b.batch, size=n_rows).astype(np.int32)
         ri = rng.integers(0, 4096, size=n_rows).astype(np.int32)
         t0 = time.perf_counter()
