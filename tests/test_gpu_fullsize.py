@@ -5,7 +5,8 @@ import numpy as np
 import pytest
 import torch
 
-from gpu_helpers import DevBatch, check_close, gpu_append, gpu_decode, gpu_prefill, gpu_resume, make_cache, to_dev
+from gpu_helpers import (DevBatch, check_close, gpu_append, gpu_decode, gpu_merged, gpu_prefill, gpu_resume, make_cache,
+                         to_dev)
 from helpers import fresh_pools, oracle_append, oracle_attn
 from oracle import oracle as O
 from paper_2603_10342_amd import inputs as I
@@ -112,3 +113,18 @@ def test_config5_shapes_sampled():
     got = gpu_decode(cache, dd.q, dd.bt, dd.ctx, dd.max_ctx, g)
     ref = O.decode(kp, vp, g.dtype, m.decode.q, m.decode.block_tables, m.decode.ctx_lens, g.num_q_heads, g.scale)
     check_close(got, ref, g.dtype, "config 5 decode")
+
+
+def test_decode_queue_merged_full():
+    """The merged workload bench.py times (64 decodes + 8 resume chunks on long prefixes): every row."""
+    c = I.make_decode_queue()
+    g = c.geom
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    for b in (c.fill, c.chunk):
+        gpu_append(cache, DevBatch(b))
+        oracle_append(kp, vp, b)
+    torch.cuda.synchronize()
+    pools_equal_on_device(cache, kp, vp, g.dtype)
+    got = gpu_merged(cache, DevBatch(c.chunk))
+    check_close(got, oracle_attn(kp, vp, c.chunk), g.dtype, "decode queue, merged")
