@@ -4,22 +4,31 @@
 //
 // A session brings N >= 0 new query rows at positions P .. P + N - 1 (a decode is N = 1) that attend causally
 // to the session's keys: the semantics of the resume prefill.  The work is cut the way the decode step cuts
-// it, because with few query rows per session the kernel is bound by reading K and V, not by arithmetic:
+// it - the keys a session's rows may see are split over workgroups, partial (m, l, O) per split, merged in
+// split order - because with few rows per session the launch is bound by reading K and V:
 //
-//   plan kernel     lists the items: an item is up to R groups of tq = 16 / G consecutive rows of one session
-//                   (G = query heads per KV head), so that a group's tq x G (row, head) pairs fill the 16
-//                   columns of the matrix instruction that the decode step leaves mostly empty; also notes
-//                   each row's session.
-//   split kernel    one workgroup per (item, KV head, split of the keys the item's last row may see); the
-//                   decode step's loop, with a visibility limit per column instead of per session.
+//   plan kernel     lists the items.  A group is tq = 16 / G consecutive rows of one session (G = query heads
+//                   per KV head): its tq x G (row, head) pairs fill the 16 columns of the matrix instruction
+//                   that the decode step leaves mostly empty.  Two kinds of item:
+//                     keys item  up to R groups; the four waves of a workgroup split the KEYS of the part, as in
+//                                the decode step, each K / V step loaded once into registers for the R groups;
+//                     rows item  up to 4 R groups (32 rows at G = 4, R = 2); the four waves split the ROWS and
+//                                all walk the same keys, which the workgroup brings into LDS once per step by
+//                                direct global-to-LDS loads (two stages), so a session's keys are fetched once
+//                                per 4 R groups instead of once per R.
+//                   Sessions with at most R groups of rows (decodes among them) become one keys item; longer
+//                   chunks become rows items plus, for a remainder of at most R groups, one keys item.
+//   split kernel    one workgroup per (item, KV head, split of the keys the item's last row may see), with a
+//                   visibility limit per column.
 //   merge kernel    one workgroup per (row, head) combines the splits in split order.
 //
-// K and V of a session are fetched by each of its items; items of one (session, KV head, split) are dealt to
-// the same XCD (their linear workgroup ids differ by a multiple of 8 when splits * KV heads is one such), so the
-// repeats are served by that XCD's L2.
+// Items of one (session, KV head, split) are dealt to the same XCD (their linear workgroup ids differ by a
+// multiple of splits * KV heads, itself a multiple of 8 at 8 KV heads), so what they fetch again comes from
+// that XCD's L2.
 #include <algorithm>
 
 #include "attn_split_common.h"
+#include "lds_dma.h"
 
 namespace ag {
 
@@ -27,31 +36,31 @@ namespace {
 
 using namespace splitk;
 
-// plan[0] = number of items, plan[2 + 2i] = session, plan[3 + 2i] = (first row of item i) / (rows per item, `tq` here);
-// row_sess[row] = session of query row `row`.  Block 0 lists the items, the other blocks the rows.
+enum { kKeysItem = 0, kRowsItem = 1 };
+
+// plan[0] = number of items; item i is plan[4 + 4i ..]: session, first row (within the session's chunk), rows, kind.
+// row_item[row] = the item that holds query row `row`.
+// rk: rows of a full keys item; rw: rows of a full rows item, 0 if the launch has no rows items.
+__device__ __forceinline__ int items_of(int n, int rk, int rw)
+{
+    if (rw == 0) return (n + rk - 1) / rk;
+    return n / rw + (n % rw ? 1 : 0);
+}
+
 __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restrict__ new_lens,
                                                           const int32_t* __restrict__ cu_new, int batch,
-                                                          int total_rows, int tq, int32_t* __restrict__ plan,
-                                                          int32_t* __restrict__ row_sess)
+                                                          int total_rows, int rk, int rw,
+                                                          int32_t* __restrict__ plan,
+                                                          int32_t* __restrict__ row_item)
 {
-    if (blockIdx.x > 0) {
-        const int row = (blockIdx.x - 1) * 256 + threadIdx.x;
-        if (row >= total_rows) return;
-        int lo = 0, hi = batch;                     // largest s with cu_new[s] <= row (empty sessions skipped)
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (cu_new[mid] <= row) lo = mid; else hi = mid;
-        }
-        row_sess[row] = lo;
-        return;
-    }
     __shared__ int scan[256];
     __shared__ int carry;
     if (threadIdx.x == 0) carry = 0;
     __syncthreads();
     for (int base = 0; base < batch; base += 256) {
         const int s = base + threadIdx.x;
-        const int mine = s < batch ? (new_lens[s] + tq - 1) / tq : 0;
+        const int n = s < batch ? new_lens[s] : 0;
+        const int mine = items_of(n, rk, rw);
         scan[threadIdx.x] = mine;
         __syncthreads();
         for (int off = 1; off < 256; off <<= 1) {   // inclusive scan
@@ -61,46 +70,42 @@ __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restr
             __syncthreads();
         }
         const int first = carry + scan[threadIdx.x] - mine;
-        for (int i = 0; i < mine; ++i) {
-            plan[2 + 2 * (first + i)] = s;
-            plan[3 + 2 * (first + i)] = i;
+        const int step = rw ? rw : rk;
+        for (int i = 0; i < mine && first + i < total_rows; ++i) {     // (lengths that contradict the host's total
+            const int t0 = i * step;                                    //  never write past the plan)
+            const int nt = min(step, n - t0);
+            int32_t* e = plan + 4 + 4 * (first + i);
+            e[0] = s; e[1] = t0; e[2] = nt;
+            e[3] = (rw && nt > rk) ? kRowsItem : kKeysItem;
+            const int row0 = cu_new[s] + t0;
+            for (int x = 0; x < nt && row0 + x < total_rows; ++x) row_item[row0 + x] = first + i;
         }
         __syncthreads();
         if (threadIdx.x == 255) carry += scan[255];
         __syncthreads();
     }
-    if (threadIdx.x == 0) { plan[0] = carry; plan[1] = tq; }
+    if (threadIdx.x == 0) plan[0] = min(carry, total_rows);
 }
 
-// kSteps: steps of 32 keys a wave may walk; the split size is 128 * kSteps keys.
-// R: column groups per item.  An item is R * tq rows; each K / V step is loaded once and used by the R groups
-// one after the other, which divides the number of times a session's keys are fetched by R at the price of
-// R times the accumulators (fewer waves per SIMD).
-template <int kSteps, int R>
-__global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnArgs a, float* __restrict__ ws_o,
-                                                                           float* __restrict__ ws_ml,
-                                                                           const int32_t* __restrict__ plan,
-                                                                           int n_splits_max, int tq)
-{
-    constexpr int kSplit = 128 * kSteps;
-    __shared__ float s_o[4][16][D];     // per wave, per column of one group: unnormalised O
-    __shared__ float s_m[4][16];
-    __shared__ float s_l[4][16];
+constexpr int kSmemBytes = 4 * 16 * D * 4 + 2 * 4 * 16 * 4;     // 33280: partials of four waves, or two K/V stages
 
-    const int split = blockIdx.x, g = blockIdx.y, item = blockIdx.z;
-    if (item >= plan[0]) return;
-    const int rows_item = R * tq;
-    const int s = plan[2 + 2 * item];
-    const int t0 = plan[3 + 2 * item] * rows_item;   // first row of the item within the session's chunk
-    const int N = a.new_lens[s];
-    const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
-    const int nt = min(rows_item, N - t0);           // rows of this item, >= 1
-    const int ctx_all = P + N;                       // slots below this hold tokens
-    const int ctx = P + t0 + nt;                     // keys the item's last row may see
-    const int part = part_tokens(ctx, kSplit);
-    const int start = split * part;
-    if (start >= ctx) return;                        // uniform over the workgroup
-    const int wave_tok = part >> 2;
+struct ItemCtx {        // what both kinds of item need; uniform over the workgroup
+    int s, t0, nt, split, g;
+    int P, ctx_all, ctx, start, part;
+};
+
+// ---- keys item: the decode step's loop with R column groups --------------------------------------------------
+template <int kSteps, int R>
+__device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
+                                          int n_splits_max, int tq, const ItemCtx& it, unsigned char* smem)
+{
+    float (*s_o)[16][D] = reinterpret_cast<float (*)[16][D]>(smem);                 // per wave, per column of one group
+    float (*s_m)[16] = reinterpret_cast<float (*)[16]>(smem + 4 * 16 * D * 4);
+    float (*s_l)[16] = s_m + 4;
+
+    const int s = it.s, t0 = it.t0, nt = it.nt, split = it.split, g = it.g;
+    const int P = it.P, ctx_all = it.ctx_all, ctx = it.ctx, start = it.start;
+    const int wave_tok = it.part >> 2;
 
     const int hkv = a.c.hkv, hq = a.hq;
     const int G = hq / hkv;
@@ -259,20 +264,207 @@ __global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnA
     }
 }
 
+// ---- rows item: four waves x R groups of rows over the same keys, K / V steps staged in LDS -------------------
+// LDS stage: K page A, K page B (each 4 KiB as stored, [chunk][slot][8 channels]; page B sits 128 bytes further
+// than a multiple of 256 so that the two pages' rows fall on different banks), V page A, V page B (4 KiB each,
+// [half][channel][8 keys]).  Wave w copies block w of the stage: four 1 KiB wave-wide loads.
+constexpr int kKPage = 4096 + 128;
+constexpr int kStage = 2 * kKPage + 2 * 4096;       // 16640
+static_assert(2 * kStage <= kSmemBytes, "two stages must fit the shared buffer");
+
+template <int kSteps, int R>
+__device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
+                                          int n_splits_max, int tq, const ItemCtx& it, unsigned char* smem)
+{
+    static_assert(kSteps <= 8, "a part of a rows item spans at most 64 pages (one page id per lane)");
+    const int s = it.s, t0 = it.t0, nt = it.nt, split = it.split, g = it.g;
+    const int P = it.P, ctx_all = it.ctx_all, ctx = it.ctx, start = it.start;
+    const int end = min(ctx, start + it.part);
+    const int n_steps = (end - start + 31) >> 5;             // >= 1, uniform over the workgroup
+
+    const int hkv = a.c.hkv, hq = a.hq;
+    const int G = hq / hkv;
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wu = __builtin_amdgcn_readfirstlane(w);        // the same value, known to be uniform
+    const int r = lane & 15, c = lane >> 4;
+
+    // this wave's rows: groups j = 0..R-1 are rows wrow0 + j * tq + (0..tq-1) of the item
+    const int wrow0 = w * R * tq;
+    const bool wave_on = wrow0 < nt;                          // uniform over the wave
+    const int pos_hi = P + t0 + min(nt, wrow0 + R * tq) - 1;  // last key any row of this wave may see
+    const int col_row = r / G, col_head = r - col_row * G;
+    int pos[R];
+    bf16x8 qf[R][4];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        const int row = wrow0 + j * tq + col_row;
+        const bool on = col_row < tq && row < nt;
+        pos[j] = P + t0 + (on ? row : nt - 1);
+        const int64_t q_row = (int64_t)a.cu_new[s] + t0 + (on ? row : 0);
+        const __bf16* qrow = (const __bf16*)a.q + (q_row * hq + (int64_t)g * G + col_head) * D + c * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            bf16x8 x = ld16(qrow + kk * 32);
+            if (!on) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+            qf[j][kk] = x;
+        }
+    }
+
+    // physical pages of the part, one per lane (clamped to the last page the item's rows may see)
+    const int n_pages_ctx = (ctx + PS - 1) >> 4;
+    const int my_pid = a.bt[(int64_t)s * a.max_pages + min((start >> 4) + lane, n_pages_ctx - 1)];
+
+    // wave w brings in block w of a stage: K page A, K page B, V page A, V page B of the step
+    const unsigned char* const pool = (const unsigned char*)(wu < 2 ? a.c.k : a.c.v);
+    const unsigned blk_off = wu < 2 ? (unsigned)(wu & 1) * kKPage : 2u * kKPage + (unsigned)(wu & 1) * 4096u;
+    auto request = [&](int st) {
+        const int64_t pid = __builtin_amdgcn_readlane(my_pid, 2 * st + (wu & 1));
+        const unsigned char* src = pool + (pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 16;
+        const unsigned dst = lds_address(smem) + (unsigned)(st & 1) * kStage + blk_off;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) load_to_lds(src + i * 1024, dst + i * 1024);
+    };
+
+    const float sl2 = a.scale * kLog2e;
+    float m[R], lsum[R];
+    f32x4 o[R][8];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        m[j] = -INFINITY;
+        lsum[j] = 0.0f;
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb) o[j][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+
+    // operand addresses inside a stage, the decode step's lane assignment: score row r is slot (r & 7) of page
+    // (r >> 3), lane group c holds channels kk * 32 + c * 8 .. + 7; value rows are channels mb * 16 + r for the
+    // 8 keys of chunk (c & 1) of page (c >> 1)
+    const int k_lane = (r >> 3) * kKPage + (c * PS + (r & 7)) * 16;           // + kk * 1024; + 128 for slots 8..15
+    const int v_lane = 2 * kKPage + (c >> 1) * 4096 + ((c & 1) * D + r) * 16;   // + mb * 256
+
+    request(0);
+#pragma unroll 1
+    for (int st = 0; st < n_steps; ++st) {
+        AG_WAIT_VMCNT(0);                            // this wave's block of step st has landed
+        __syncthreads();                             // ... and everybody's; all waves are done with step st - 1
+        if (st + 1 < n_steps) request(st + 1);       // into the stage step st - 1 was read from
+        const int tok0 = start + st * 32;
+        if (wave_on && tok0 <= pos_hi) {
+            const unsigned char* stage = smem + (st & 1) * kStage;
+            const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
+            f32x4 s1[R], s2[R];
+#pragma unroll
+            for (int j = 0; j < R; ++j) { s1[j] = f32x4{0.f, 0.f, 0.f, 0.f}; s2[j] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024);
+                const bf16x8 k2 = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024 + 128);
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    s1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[j][kk], s1[j], 0, 0, 0);
+                    s2[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2, qf[j][kk], s2[j], 0, 0, 0);
+                }
+            }
+            bf16x8 pb[R];
+            float alpha[R];
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                const int keep = pos[j] + 1 - tokb;  // key tokb + i is visible to this column iff i < keep
+                float xs[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    xs[i] = (i < keep) ? s1[j][i] * sl2 : -INFINITY;
+                    xs[4 + i] = (8 + i < keep) ? s2[j][i] * sl2 : -INFINITY;
+                }
+                float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
+                mx = fmaxf(mx, __shfl_xor(mx, 16));
+                mx = fmaxf(mx, __shfl_xor(mx, 32));
+                const float m_new = fmaxf(m[j], mx);
+                const float m_ref = m_new == -INFINITY ? 0.f : m_new;       // see keys_item
+                alpha[j] = __builtin_amdgcn_exp2f(m[j] - m_ref);
+                float psum = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
+                    psum += p;
+                    pb[j][e] = (__bf16)p;
+                }
+                lsum[j] = lsum[j] * alpha[j] + psum;
+                m[j] = m_new;
+            }
+            const bool tail = tok0 + 32 > ctx_all;   // slots past the session's last token may hold anything
+            const int keep_v = ctx_all - tokb;
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) {
+                bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + v_lane + mb * 256);
+                if (tail) v = keep_quads(v, keep_v, keep_v - 8);
+#pragma unroll
+                for (int j = 0; j < R; ++j) {
+                    o[j][mb] *= alpha[j];
+                    o[j][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, pb[j], o[j][mb], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // every wave holds the whole part for its rows: partials go straight to the workspace
+    if (wave_on) {
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int row = wrow0 + j * tq + col_row;
+            float l = lsum[j];
+            l += __shfl_xor(l, 16);
+            l += __shfl_xor(l, 32);
+            if (col_row < tq && row < nt) {
+                const int64_t slot = (((int64_t)a.cu_new[s] + t0 + row) * hq + (int64_t)g * G + col_head) * n_splits_max + split;
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(ws_o + slot * D + mb * 16 + c * 4) = o[j][mb];
+                if (c == 0) { ws_ml[slot * 2] = m[j]; ws_ml[slot * 2 + 1] = l; }
+            }
+        }
+    }
+}
+
+// kSteps: the split size is 128 * kSteps keys.  R: column groups per wave.  kRows: the launch has rows items.
+template <int kSteps, int R, bool kRows>
+__global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnArgs a, float* __restrict__ ws_o,
+                                                                           float* __restrict__ ws_ml,
+                                                                           const int32_t* __restrict__ plan,
+                                                                           int n_splits_max, int tq)
+{
+    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+    const int item = blockIdx.z;
+    if (item >= plan[0]) return;
+    const int32_t* e = plan + 4 + 4 * item;
+    ItemCtx it;
+    it.s = e[0]; it.t0 = e[1]; it.nt = e[2];
+    const int kind = e[3];
+    it.split = blockIdx.x; it.g = blockIdx.y;
+    const int N = a.new_lens[it.s];
+    it.P = a.prefix_lens ? a.prefix_lens[it.s] : 0;
+    it.ctx_all = it.P + N;                           // slots below this hold tokens
+    it.ctx = it.P + it.t0 + it.nt;                   // keys the item's last row may see
+    it.part = part_tokens(it.ctx, 128 * kSteps);
+    it.start = it.split * it.part;
+    if (it.start >= it.ctx) return;                  // uniform over the workgroup
+    if constexpr (kRows) {
+        if (kind == kRowsItem) { rows_item<kSteps, R>(a, ws_o, ws_ml, n_splits_max, tq, it, smem); return; }
+    }
+    keys_item<kSteps, R>(a, ws_o, ws_ml, n_splits_max, tq, it, smem);
+}
+
 __global__ __launch_bounds__(128) void merged_merge_kernel(AttnArgs a, const float* __restrict__ ws_o,
                                                            const float* __restrict__ ws_ml,
-                                                           const int32_t* __restrict__ row_sess, int n_splits_max,
-                                                           int split_tokens, int rows_item)
+                                                           const int32_t* __restrict__ plan,
+                                                           const int32_t* __restrict__ row_item, int n_splits_max,
+                                                           int split_tokens)
 {
     const int64_t rh = blockIdx.x;                 // row * hq + head
     const int row = (int)(rh / a.hq);
     const int d = threadIdx.x;
-    const int s = row_sess[row];
-    const int t = row - a.cu_new[s];
-    const int N = a.new_lens[s];
-    const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
-    const int t0 = (t / rows_item) * rows_item;
-    const int ctx = P + t0 + min(rows_item, N - t0);      // as the split kernel cut the row's item
+    const int32_t* e = plan + 4 + 4 * row_item[row];
+    const int P = a.prefix_lens ? a.prefix_lens[e[0]] : 0;
+    const int ctx = P + e[1] + e[2];               // as the split kernel cut the row's item
     const int part = part_tokens(ctx, split_tokens);
     const int n = (ctx + part - 1) / part;
     const int64_t base = rh * n_splits_max;
@@ -287,13 +479,17 @@ __global__ __launch_bounds__(128) void merged_merge_kernel(AttnArgs a, const flo
     ((__bf16*)a.out)[rh * D + d] = (__bf16)(acc / l);
 }
 
-inline int rows_per_item(int hq, int hkv) { return 16 / (hq / hkv); }
+inline int rows_per_group(int hq, int hkv) { return 16 / (hq / hkv); }
 
-inline int choose_split(int items, int hkv, int max_ctx)
+inline int choose_split(int64_t items, int hkv, int max_ctx, int largest)
 {
-    const int64_t want = 4 * 256;            // workgroups, counting contexts at about 60 % of max_ctx
-    for (int split = 2048; split > kMinSplit; split >>= 1) {
-        const int64_t wgs = (int64_t)items * hkv * ((6 * (int64_t)max_ctx / 10 + split - 1) / split);
+    // As long as possible (every workgroup pays a fixed start-up) while the launch still has about eight
+    // workgroups per CU, counting contexts at about 60 % of max_ctx: a queue that mixes a few long resume
+    // prefixes with many shorter decode contexts is far below that estimate, and one round of long workgroups
+    // balances badly.
+    const int64_t want = 8 * 256;
+    for (int split = largest; split > kMinSplit; split >>= 1) {
+        const int64_t wgs = items * hkv * ((6 * (int64_t)max_ctx / 10 + split - 1) / split);
         if (wgs >= want) return split;
     }
     return kMinSplit;
@@ -303,7 +499,21 @@ struct Layout { size_t o_floats, ml_floats, plan_ints, row_ints; };
 inline Layout layout(int total_rows, int hq, int max_ctx)
 {
     const size_t nsm = (size_t)splits_for(max_ctx, kMinSplit);
-    return {(size_t)total_rows * hq * nsm * D, (size_t)total_rows * hq * nsm * 2, 2 + 2 * (size_t)total_rows, (size_t)total_rows};
+    return {(size_t)total_rows * hq * nsm * D, (size_t)total_rows * hq * nsm * 2, 4 + 4 * (size_t)total_rows, (size_t)total_rows};
+}
+
+template <int R, bool kRows>
+void launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml,
+                  const int32_t* plan, int nsm, int tq)
+{
+    switch (split) {
+        case 2048:
+            if constexpr (!kRows) { hipLaunchKernelGGL((merged_split_kernel<16, R, false>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break; }
+            [[fallthrough]];     // not chosen for launches with rows items
+        case 1024: hipLaunchKernelGGL((merged_split_kernel<8, R, kRows>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+        case 512:  hipLaunchKernelGGL((merged_split_kernel<4, R, kRows>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+        default:   hipLaunchKernelGGL((merged_split_kernel<2, R, kRows>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+    }
 }
 
 }  // namespace
@@ -321,53 +531,48 @@ bool merged_mfma_supported(const AttnArgs& a)
            (((uintptr_t)a.q | (uintptr_t)a.c.k | (uintptr_t)a.c.v) % 16 == 0);
 }
 
-template <int R>
-static void launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml,
-                         const int32_t* plan, int nsm, int tq)
-{
-    switch (split) {
-        case 2048: hipLaunchKernelGGL((merged_split_kernel<16, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        case 1024: hipLaunchKernelGGL((merged_split_kernel<8, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        case 512:  hipLaunchKernelGGL((merged_split_kernel<4, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        default:   hipLaunchKernelGGL((merged_split_kernel<2, R>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-    }
-}
-
 ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
     if (a.total_rows <= 0) return AG_OK;
-    const int tq = rows_per_item(a.hq, a.c.hkv);
-    // Two column groups per item as soon as some session may bring more rows than one group holds: its keys
-    // are then fetched half as often.  A batch of decodes only keeps one group (and twice the waves per SIMD).
-#ifdef AG_MERGED_FORCE_R
-    const int R = AG_MERGED_FORCE_R;
-#else
+    const int tq = rows_per_group(a.hq, a.c.hkv);
+    // A batch of decodes only (no session brings more rows than one group holds): one group per item, four
+    // waves per SIMD.  Otherwise two groups per wave: keys items of up to 2 tq rows, and - once some session
+    // may bring more than that - rows items of up to 8 tq rows.
     const int R = a.max_new > tq ? 2 : 1;
+#ifdef AG_MERGED_NO_ROWS_ITEMS
+    const bool rows = false;
+#else
+    const bool rows = a.max_new > R * tq;
 #endif
-    const int rows_item = R * tq;
-    // every item has at least one row, and a session of N rows has ceil(N / rows_item) items
-    const int64_t items_max = std::min<int64_t>(a.total_rows, ((int64_t)a.total_rows + (int64_t)a.batch * (rows_item - 1)) / rows_item);
+    const int rk = R * tq, rw = rows ? 4 * R * tq : 0;
+    // a session of N rows has at most N / (rows per full item) + 1 items, and every item has at least one row
+    const int64_t items_max = std::min<int64_t>(a.total_rows, (int64_t)a.total_rows / (rw ? rw : rk) + a.batch);
     if (items_max > 65535 || a.c.hkv > 65535) { set_error("too many items (%lld) or KV heads for one launch grid", (long long)items_max); return AG_ERR_INVALID_ARG; }
-    const int split = choose_split((int)items_max, a.c.hkv, a.max_ctx);
+#ifdef AG_MERGED_FORCE_SPLIT
+    const int split = AG_MERGED_FORCE_SPLIT;
+#else
+    const int split = choose_split(items_max, a.c.hkv, a.max_ctx, rows ? 1024 : 2048);
+#endif
     const int nsm = splits_for(a.max_ctx, split);
     const Layout L = layout(a.total_rows, a.hq, a.max_ctx);
     float* ws_o = (float*)ws;
     float* ws_ml = ws_o + L.o_floats;
     int32_t* plan = (int32_t*)(ws_ml + L.ml_floats);
-    int32_t* row_sess = plan + L.plan_ints;
+    int32_t* row_item = plan + L.plan_ints;
 
-    hipLaunchKernelGGL(merged_plan_kernel, dim3(1 + (a.total_rows + 255) / 256), dim3(256), 0, st, a.new_lens, a.cu_new,
-                       a.batch, a.total_rows, rows_item, plan, row_sess);
+    hipLaunchKernelGGL(merged_plan_kernel, dim3(1), dim3(256), 0, st, a.new_lens, a.cu_new, a.batch, a.total_rows, rk, rw,
+                       plan, row_item);
     ag_status e = hip_check(hipGetLastError(), "merged plan launch");
     if (e) return e;
     const dim3 grid(nsm, a.c.hkv, (unsigned)items_max);
     prof_before(st);
-    if (R == 2) launch_split<2>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-    else launch_split<1>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    if (R == 1) launch_split<1, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    else if (!rows) launch_split<2, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    else launch_split<2, true>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
     prof_after(st);
     if ((e = hip_check(hipGetLastError(), "merged split launch"))) return e;
     hipLaunchKernelGGL(merged_merge_kernel, dim3((unsigned)((int64_t)a.total_rows * a.hq)), dim3(128), 0, st, a, ws_o, ws_ml,
-                       row_sess, nsm, split, rows_item);
+                       plan, row_item, nsm, split);
     return hip_check(hipGetLastError(), "merged merge launch");
 }
 
