@@ -106,11 +106,11 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
         const __bf16* vp = vpool + ((v_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + v_off;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            x.k1[kk] = ld16(kp + kk * 4 * PS * 8);
-            x.k2[kk] = ld16(kp + kk * 4 * PS * 8 + 64);
+            x.k1[kk] = ld16_stream(kp + kk * 4 * PS * 8);
+            x.k2[kk] = ld16_stream(kp + kk * 4 * PS * 8 + 64);
         }
 #pragma unroll
-        for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16(vp + mb * 16 * 8);
+        for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16_stream(vp + mb * 16 * 8);
     };
 
     auto compute_step = [&](int st, StepRegs& x) {
@@ -254,7 +254,11 @@ bool decode_mfma_supported(const AttnArgs& a)
 
 ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
+#ifdef AG_DECODE_FORCE_SPLIT
+    const int split = AG_DECODE_FORCE_SPLIT;
+#else
     const int split = choose_split(a.batch, a.c.hkv, a.max_ctx);
+#endif
     const int nsm = splits_for(a.max_ctx, split);
     float* ws_o = (float*)ws;
     float* ws_ml = ws_o + (size_t)a.batch * a.hq * nsm * D;

@@ -173,11 +173,11 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
                 const __bf16* vp = vpool + ((v_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + v_off;
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
-                    x.k1[kk] = ld16(kp + kk * 4 * PS * 8);
-                    x.k2[kk] = ld16(kp + kk * 4 * PS * 8 + 64);
+                    x.k1[kk] = ld16_stream(kp + kk * 4 * PS * 8);
+                    x.k2[kk] = ld16_stream(kp + kk * 4 * PS * 8 + 64);
                 }
 #pragma unroll
-                for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16(vp + mb * 16 * 8);
+                for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16_stream(vp + mb * 16 * 8);
             }
             const int tok0 = wstart + st * 32;
             const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
