@@ -465,38 +465,89 @@ def bench_merged(args, torch, B, I):
 
 
 # --------------------------------------------------------------------------- closed loop (Algorithm 1)
+class ServingLoad:
+    """Config 5's sessions with resume chunks of mixed length on one cache, cut into the scheduler's two queues
+    for every admission level (inputs.make_serving): the decode queue runs as one merged launch, the prefill
+    queue as cold prefill + resume prefill of what was not admitted."""
+
+    def __init__(self, torch, B, I, n_decode, levels):
+        c = I.make_serving(n_decode=n_decode)
+        g = c.geom
+        self.B, self.g, self.c = B, g, c
+        self.cache = cache = B.KVCache(g.num_pages, g.page_size, g.num_kv_heads, g.head_dim, g.dtype, fill=0.0)
+        for f in (c.resume_fill, c.decode_fill):
+            d = Dev(f, torch)
+            B.ag_kv_append(cache, d.k_new, d.v_new, d.bt, d.prefix, d.new, d.cu, d.total)
+        self.cold = Dev(c.cold, torch)
+        self.qd = {a: Dev(c.queue_d[a], torch) for a in levels}
+        self.qp = {a: (Dev(c.queue_p[a], torch) if c.queue_p[a] is not None else None) for a in levels}
+        need = max(B.ag_attn_merged_workspace_bytes(d.total, g.num_q_heads, d.max_ctx) for d in self.qd.values())
+        self.ws = torch.empty(need // 4, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        self.prefill_tokens = {a: self.cold.total + (self.qp[a].total if self.qp[a] is not None else 0) for a in levels}
+
+    def level_for(self, b_prefill):
+        return int((self.c.resume_lens <= b_prefill).sum())
+
+    def decode_step(self, st, a):
+        B, g, d = self.B, self.g, self.qd[a]
+        B.ag_kv_append(self.cache, d.k_new, d.v_new, d.bt, d.prefix, d.new, d.cu, d.total, stream=st)
+        B.ag_attn_merged(self.cache, d.q, d.out, d.bt, d.prefix, d.new, d.cu, d.total, d.max_new, d.max_ctx,
+                         g.num_q_heads, g.scale, self.ws, stream=st)
+
+    def prefill_loop(self, st, a):
+        B, g, cold, res, cache = self.B, self.g, self.cold, self.qp[a], self.cache
+        B.ag_kv_append(cache, cold.k_new, cold.v_new, cold.bt, cold.prefix, cold.new, cold.cu, cold.total, stream=st)
+        B.ag_attn_prefill(cache, cold.q, cold.out, cold.bt, cold.new, cold.cu, cold.total, cold.max_new,
+                          g.num_q_heads, g.scale, stream=st)
+        if res is not None:
+            B.ag_kv_append(cache, res.k_new, res.v_new, res.bt, res.prefix, res.new, res.cu, res.total, stream=st)
+            B.ag_attn_resume(cache, res.q, res.out, res.bt, res.prefix, res.new, res.cu, res.total, res.max_new,
+                             res.max_ctx, g.num_q_heads, g.scale, stream=st)
+
+
 def bench_controller(args, torch, B, I, info):
-    """Config 5's load under the TPOT-driven controller (paper Sec. III-B, Algorithm 1) and the table of
-    pre-established partitions (Sec. III-C): a decode thread and a prefill thread submit to the streams of the
-    currently bound entry; the scheduler closes a control interval every dt, moves R_min / B_prefill and
-    rebinds.  Reports the trajectory, where it settles, and what a rebinding costs."""
-    load = MixedLoad(torch, B, I)
+    """The paper's loop on config 5's sessions (Sec. III-B, Algorithm 1; Sec. III-C): resume chunks no longer
+    than B_prefill join the decodes in the decode queue, which a decode thread runs as one merged launch per
+    step on the decode partition; cold prefills and the longer chunks form the prefill queue, which a prefill
+    thread runs on the complementary partition; the scheduler closes a control interval every dt, moves
+    R_min / B_prefill and rebinds.  Halfway three quarters of the decoding sessions leave.  Reports the
+    trajectory, where it settles, and what a rebinding costs.  (Both threads re-run their queue at fixed
+    positions, so latencies are stationary; while an admission level changes, the two threads may for one
+    iteration both hold the same chunk: timing only, results are not checked here.)"""
     g_units = 4
+    b_min, b_max, d_b = 64, 512, 64
+    lens = np.asarray([16, 32, 64, 96, 128, 256, 384, 512])
+    levels = sorted({int((lens <= b).sum()) for b in range(b_min, b_max + 1, d_b)} | {0})
+    heavy = ServingLoad(torch, B, I, 64, levels)
+    light = ServingLoad(torch, B, I, 16, levels)
     slots = B.Slots(g_units)
     S = slots.units()
     entries = [slots.get(i) for i in range(slots.count())]
     old_si = sys.getswitchinterval()
     sys.setswitchinterval(1e-5)
-    out = {"g_units": g_units, "S": S, "entries": [e["decode_units"] for e in entries]}
+    out = {"g_units": g_units, "S": S, "entries": [e["decode_units"] for e in entries], "resume_chunk_rows": lens.tolist(),
+           "admission_levels": levels}
     try:
-        # reference: decode alone on the whole device, same loop shape
+        # reference: the decodes alone (no chunk admitted) on the whole device, same loop shape
         lat = []
         for i in range(300):
             t0 = time.perf_counter()
-            load.decode_step(None)
+            heavy.decode_step(None, 0)
             torch.cuda.current_stream().synchronize()
             if i >= 100:
                 lat.append((time.perf_counter() - t0) * 1e6)
         alone = pct(lat, 50)
-        params = dict(S=S, r_base=g_units, r_init=g_units, b_init=512, delta_r=g_units, delta_b=128, b_min=128,
-                      b_max=1024, theta_low_us=1.2 * alone, theta_high_us=1.5 * alone)
+        params = dict(S=S, r_base=g_units, r_init=g_units, b_init=b_max, delta_r=g_units, delta_b=d_b, b_min=b_min,
+                      b_max=b_max, theta_low_us=1.3 * alone, theta_high_us=1.7 * alone)
         ctl = B.Controller(**params)
         dt = args.ctl_interval_ms / 1e3
         stop = threading.Event()
         cur = [slots.bind(params["r_init"])]
-        nsess = [load.dec.b.batch]                  # sessions decoding: all in the first half, a quarter afterwards
+        adm = [heavy.level_for(params["b_init"])]
+        load = [heavy]
         dec_lat, dec_after_rebind = [], []
-        loops, held = [0], [0]
+        loops, held, ptok = [0], [0], [0]
 
         def decode_thread():
             last = -1
@@ -504,7 +555,7 @@ def bench_controller(args, torch, B, I, info):
                 i = cur[0]
                 st = entries[i]["decode_stream"]
                 t0 = time.perf_counter()
-                load.decode_step(st, nsess[0])
+                load[0].decode_step(st, adm[0])
                 torch.cuda.ExternalStream(st).synchronize()
                 us = (time.perf_counter() - t0) * 1e6
                 ctl.record_decode(us)
@@ -518,9 +569,11 @@ def bench_controller(args, torch, B, I, info):
                     held[0] += 1
                     time.sleep(dt / 4)
                     continue
-                load.prefill_loop(st)
+                ld, a = load[0], adm[0]
+                ld.prefill_loop(st, a)
                 torch.cuda.ExternalStream(st).synchronize()
                 loops[0] += 1
+                ptok[0] += ld.prefill_tokens[a]
 
         td, tp = threading.Thread(target=decode_thread), threading.Thread(target=prefill_thread)
         t_start = time.perf_counter()
@@ -528,9 +581,10 @@ def bench_controller(args, torch, B, I, info):
         tp.start()
         traj, bind_us = [], []
         n_int = args.ctl_intervals
+        n_heavy_steps = 0
         for k in range(n_int):
             if k == n_int // 2:
-                nsess[0] = max(1, load.dec.b.batch // 4)
+                load[0] = light
                 n_heavy_steps = len(dec_lat)
             time.sleep(dt)
             st = ctl.tick()
@@ -538,43 +592,39 @@ def bench_controller(args, torch, B, I, info):
             i = slots.bind(st["r_min"])
             cur[0] = i
             bind_us.append((time.perf_counter() - t0) * 1e6)
+            adm[0] = heavy.level_for(st["b_prefill"])
             traj.append({"t_ms": (time.perf_counter() - t_start) * 1e3, "tpot_us": st["tpot_us"], "r_min": st["r_min"],
-                         "b_prefill": st["b_prefill"], "decode_units": entries[i]["decode_units"]})
+                         "b_prefill": st["b_prefill"], "decode_units": entries[i]["decode_units"], "admitted": adm[0]})
         stop.set()
         td.join()
         tp.join()
         wall = time.perf_counter() - t_start
         torch.cuda.synchronize()
+
         def phase(tr, lats):
             tail = tr[len(tr) // 2:]                 # second half of the phase: after the transient
             ok = [x["tpot_us"] for x in tail if x["tpot_us"] == x["tpot_us"]]
             units = tail[-1]["decode_units"]
             steady = [us for (i, us) in lats[len(lats) // 2:] if entries[i]["decode_units"] == units]
-            return {"settled_decode_units": units, "levels_seen_after_transient": sorted({x["decode_units"] for x in tail}),
+            return {"settled_decode_units": units, "settled_b_prefill": tail[-1]["b_prefill"],
+                    "settled_chunks_admitted": tail[-1]["admitted"],
+                    "levels_seen_after_transient": sorted({x["decode_units"] for x in tail}),
                     "tpot_us_mean": float(np.mean(ok)) if ok else None,
-                    "step_p50_us": pct(steady, 50) if steady else None, "step_p99_us": pct(steady, 99) if steady else None,
-                    "intervals_to_settle": next((k for k in range(len(tr)) if all(x["decode_units"] == units for x in tr[k:])), None)}
+                    "step_p50_us": pct(steady, 50) if steady else None, "step_p99_us": pct(steady, 99) if steady else None}
 
-        heavy = phase(traj[:n_int // 2], dec_lat[:n_heavy_steps])
-        light = phase(traj[n_int // 2:], dec_lat[n_heavy_steps:])
-        res_lens = load.m.resume.new_lens
         out.update({
             "params": params, "interval_ms": args.ctl_interval_ms, "intervals": n_int,
             "decode_alone_p50_us": alone,
             "trajectory_r_min": [x["r_min"] for x in traj], "trajectory_b_prefill": [x["b_prefill"] for x in traj],
             "trajectory_tpot_us": [None if x["tpot_us"] != x["tpot_us"] else round(x["tpot_us"], 1) for x in traj],
-            "phase_all_sessions": heavy, "phase_quarter_of_sessions": light,
-            "heavy_p99_over_alone_p50": heavy["step_p99_us"] / alone if heavy["step_p99_us"] else None,
+            "phase_64_decoding_sessions": phase(traj[:n_int // 2], dec_lat[:n_heavy_steps]),
+            "phase_16_decoding_sessions": phase(traj[n_int // 2:], dec_lat[n_heavy_steps:]),
             "decode_steps": len(dec_lat) + len(dec_after_rebind),
-            "prefill_tokens_per_s": loops[0] * load.prefill_tokens / wall, "prefill_loops": loops[0],
-            "prefill_held_polls": held[0],
+            "prefill_tokens_per_s": ptok[0] / wall, "prefill_loops": loops[0], "prefill_held_polls": held[0],
             "rebinds": len(dec_after_rebind),
             "rebind_host_us_mean": float(np.mean(bind_us)), "rebind_host_us_max": float(np.max(bind_us)),
             "first_step_after_rebind_us_median": pct([u for _, u in dec_after_rebind], 50) if dec_after_rebind else None,
             "epsilon_ctx_bound": float(np.max(bind_us)) / (args.ctl_interval_ms * 1e3),
-            "resume_chunks_admitted_to_decode_queue_at_end": int(sum(
-                ctl.classify(B.AG_REQ_RESUME, int(n)) == B.AG_QUEUE_DECODE for n in res_lens)),
-            "resume_chunks": int(len(res_lens)),
         })
         ctl.close()
     finally:

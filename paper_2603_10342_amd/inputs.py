@@ -411,6 +411,47 @@ def make_mixed(num_pages: int = 36864, seed: Optional[int] = None, n_cold: int =
     return MixedConfig(geom, cold, r_fill, res, d_fill, dec)
 
 
+@dataclass
+class ServingConfig:
+    """Config 5's sessions with tool outputs of mixed length, cut the way the scheduler's two queues cut them:
+    for every admission level a (the a shortest resume chunks fit the budget B_prefill), `queue_d[a]` is the
+    decode queue's batch (all decodes followed by those a chunks) and `queue_p[a]` the resume chunks left to
+    the prefill queue (None when there are none).  `cold` always belongs to the prefill queue."""
+    geom: Geometry
+    cold: Batch
+    resume_fill: Batch
+    decode_fill: Batch
+    resume_lens: np.ndarray
+    queue_d: dict
+    queue_p: dict
+
+
+def make_serving(num_pages: int = 36864, seed: Optional[int] = None, n_cold: int = 2, cold_len: int = 8192,
+                 resume_prefix: int = 4096, resume_lens=(16, 32, 64, 96, 128, 256, 384, 512), n_decode: int = 64,
+                 d_lo: int = 1024, d_hi: int = 8192, geom: Optional[Geometry] = None) -> ServingConfig:
+    seed = config_seed(7) if seed is None else seed
+    geom = slm_geometry(num_pages) if geom is None else geom
+    rng = rng_for(seed, 0)
+    lens = np.sort(np.asarray(resume_lens, np.int32))
+    n_resume = len(lens)
+    ctx = uniform_lens(rng, d_lo, d_hi, n_decode)
+    caps = [cold_len] * n_cold + [resume_prefix + int(n) for n in lens] + list(ctx)
+    bt = deal_block_tables(rng, caps, geom.page_size, geom.num_pages)
+    bt_c, bt_r, bt_d = bt[:n_cold], bt[n_cold:n_cold + n_resume], bt[n_cold + n_resume:]
+    cold = draw_batch(geom, np.ascontiguousarray(bt_c), [0] * n_cold, [cold_len] * n_cold, seed + 50, 1)
+    r_fill = draw_batch(geom, np.ascontiguousarray(bt_r), [0] * n_resume, [resume_prefix] * n_resume, seed + 50, 2)
+    d_fill = draw_batch(geom, np.ascontiguousarray(bt_d), np.zeros(n_decode, np.int32), ctx - 1, seed + 50, 3)
+    queue_d, queue_p = {}, {}
+    for a in range(n_resume + 1):
+        bt_q = np.ascontiguousarray(np.concatenate([bt_d, bt_r[:a]]))
+        prefix = np.concatenate([ctx - 1, np.full(a, resume_prefix, np.int32)]).astype(np.int32)
+        new = np.concatenate([np.ones(n_decode, np.int32), lens[:a]]).astype(np.int32)
+        queue_d[a] = draw_batch(geom, bt_q, prefix, new, seed + 50, 10 + a)
+        queue_p[a] = None if a == n_resume else draw_batch(
+            geom, np.ascontiguousarray(bt_r[a:]), [resume_prefix] * (n_resume - a), lens[a:], seed + 50, 30 + a)
+    return ServingConfig(geom, cold, r_fill, d_fill, lens, queue_d, queue_p)
+
+
 # ----------------------------------------------------------------------------
 # adversarial value patterns (data only)
 # ----------------------------------------------------------------------------
