@@ -2,6 +2,8 @@
 """Benchmark of the paged-KV attention hot path on one MI355X.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads decode,cold,resume,mixed]
+  further workloads, not in the default run: merged (the decode queue in one launch), controller (the
+  TPOT-driven loop on partitions), cushare (throughput against CU share), copycal (counter yardstick)
 
 Prints ONE JSON line.  The headline metric is decode-attention HBM GB/s on the
 decode-only configuration (64 sessions, contexts U[1024, 4096], 32/8 heads,

@@ -46,7 +46,12 @@ __global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float*
     __shared__ float s_m[4][16];
     __shared__ float s_l[4][16];
 
-    const int split = blockIdx.x, g = blockIdx.y, s = blockIdx.z;
+    // Workgroups are dealt to the 8 XCDs round-robin in linear order (x fastest).  Short sessions only have
+    // the low split numbers, so if blockIdx.x were the split itself the XCDs that draw the low numbers would
+    // get all the work of short sessions on top of their share of long ones (with 8 splits: everything on
+    // one XCD per split).  Rotating the split by head and session spreads them evenly.
+    const int g = blockIdx.y, s = blockIdx.z;
+    const int split = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
     const int ctx = a.ctx_lens[s];
     if (ctx <= 0) return;
     const int part = part_tokens(ctx, kSplit);

@@ -439,7 +439,12 @@ __global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnA
     ItemCtx it;
     it.s = e[0]; it.t0 = e[1]; it.nt = e[2];
     const int kind = e[3];
-    it.split = blockIdx.x; it.g = blockIdx.y;
+    // Workgroups go to the XCDs round-robin in linear order (x fastest).  The split is blockIdx.x rotated by
+    // head and session: short sessions only have the low split numbers, which would otherwise pile up on the
+    // XCDs that draw them (see the decode step); rotating by the session, not the item, keeps the items of one
+    // (session, KV head, split) on one XCD, whose L2 then serves what they fetch again.
+    it.g = blockIdx.y;
+    it.split = (int)((blockIdx.x + blockIdx.y + (unsigned)it.s) % gridDim.x);
     const int N = a.new_lens[it.s];
     it.P = a.prefix_lens ? a.prefix_lens[it.s] : 0;
     it.ctx_all = it.P + N;                           // slots below this hold tokens

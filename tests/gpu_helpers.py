@@ -11,7 +11,7 @@ from paper_2603_10342_amd import inputs as I
 DEV = "cuda"
 
 # Tolerances: the stated bf16 gate (max-abs 2e-2, mean-abs 2e-3) plus stricter relative gates that make it meaningful
-# on inputs whose outputs are much smaller than the absolute bound).
+# on inputs whose outputs are much smaller than the absolute bound.
 BF16_MAX_ABS, BF16_MEAN_ABS, BF16_REL_FRO = 2e-2, 2e-3, 1e-2
 F32_MAX_ABS, F32_REL_FRO = 1e-5, 1e-5
 
