@@ -347,17 +347,33 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
             for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
             const bf16x2 kOnes = {(__bf16)1.0f, (__bf16)1.0f};
             float psum = 0.f;
+            // The vector work of a pair of scores is a chain (scale -> exp -> convert -> sum) whose links cannot
+            // issue back to back; it is spread over four steps so that nothing inside a step depends on anything
+            // else inside it: step i scales pair i + 1, takes the exp of pair i, converts pair i - 1 and sums
+            // pair i - 2.
+            auto scaled = [&](int pair, int k) { const int e = 2 * pair + k; return fmaf(sc[e >> 4][e & 15], sl2, -m); };
+            float x0 = scaled(0, 0), x1 = scaled(0, 1);          // pair 0, scaled
+            float q0 = 0.f, q1 = 0.f;                            // exp of the pair one step back
+            bf16x2 pr_prev = {(__bf16)0.f, (__bf16)0.f};         // converted pair two steps back
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (i + kAhead < 16) opnd[(i + kAhead) % (kAhead + 1)] = *reinterpret_cast<const bf16x8*>(operand(i + kAhead));
-                o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], p_prev[i >> 2], o[i & 3], 0, 0, 0);
-                const int e = 2 * i;
-                const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][e & 15], sl2, -m));
-                const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[e >> 4][(e & 15) + 1], sl2, -m));
-                const bf16x2 pr = {(__bf16)p0, (__bf16)p1};
-                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, kOnes, psum, false);   // l sums the weights as rounded
-                p_cur[e >> 3][e & 7] = pr[0];
-                p_cur[e >> 3][(e & 7) + 1] = pr[1];
+            for (int i = 0; i < 16 + 2; ++i) {
+                if (i < 16) {
+                    if (i + kAhead < 16) opnd[(i + kAhead) % (kAhead + 1)] = *reinterpret_cast<const bf16x8*>(operand(i + kAhead));
+                    o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], p_prev[i >> 2], o[i & 3], 0, 0, 0);
+                }
+                if (i >= 2) psum = __builtin_amdgcn_fdot2_f32_bf16(pr_prev, kOnes, psum, false);   // l sums the weights as rounded
+                if (i >= 1 && i <= 16) {
+                    const bf16x2 pr = {(__bf16)q0, (__bf16)q1};
+                    const int e = 2 * (i - 1);
+                    p_cur[e >> 3][e & 7] = pr[0];
+                    p_cur[e >> 3][(e & 7) + 1] = pr[1];
+                    pr_prev = pr;
+                }
+                if (i < 16) {
+                    q0 = __builtin_amdgcn_exp2f(x0);
+                    q1 = __builtin_amdgcn_exp2f(x1);
+                }
+                if (i + 1 < 16) { x0 = scaled(i + 1, 0); x1 = scaled(i + 1, 1); }
                 __builtin_amdgcn_sched_barrier(0);
             }
             lsum += psum;
