@@ -154,6 +154,19 @@ def bench_decode(args, torch, B, I):
 
     sec = time_steps(torch, one, args.steps, args.warmup)
     prof = kernel_time(B, torch, one, args.steps, args.warmup)
+    sec_graph = None
+    if args.graph:
+        # the same step recorded once per session set into a HIP graph and replayed
+        graphs = []
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        for r in range(len(sets)):
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr, stream=side):
+                one(r)
+            graphs.append(gr)
+        torch.cuda.synchronize()
+        sec_graph = time_steps(torch, lambda i: graphs[i % len(graphs)].replay(), args.steps, args.warmup)
 
     esz = 2
     kv_bytes = int(c.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
@@ -169,6 +182,9 @@ def bench_decode(args, torch, B, I):
         "kernel_GBps": attn_bytes / (prof["mean_us"] * 1e-6) / 1e9,
         "sets": len(sets), "sessions": nb, "mean_ctx": float(c.ctx_lens.mean()),
     }
+    if sec_graph is not None:
+        out["graph_replay_ms_per_step"] = sec_graph * 1e3
+        out["graph_replay_step_GBps"] = (attn_bytes + append_bytes) / sec_graph / 1e9
     log("decode", json.dumps(out))
 
     if not args.no_cpu_baseline:
@@ -742,6 +758,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=4, help="disjoint session sets the decode step rotates over")
     ap.add_argument("--mixed-steps", type=int, default=1000)
+    ap.add_argument("--graph", action="store_true", help="decode workload: also time the step replayed from a HIP graph")
     ap.add_argument("--merged-rows", default="16,64", help="range of the resume chunks' rows in the merged workload")
     ap.add_argument("--ctl-interval-ms", type=float, default=20.0, help="control interval of the closed-loop workload")
     ap.add_argument("--ctl-intervals", type=int, default=100)
