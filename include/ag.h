@@ -191,7 +191,11 @@ AG_API ag_status ag_stream_destroy(void* stream);
  * and mask bit b addresses XCD b % n_xcd, CU b / n_xcd of that XCD.  Sets the
  * bits of CUs [first_cu_per_xcd, first_cu_per_xcd + cus_per_xcd) of each XCD;
  * total_cus = n_xcd * (CUs per XCD).  Paper Eq. for the discrete allocation
- * set {g, 2g, ..., S}: here g = n_xcd CUs.
+ * set {g, 2g, ..., S}: here g = n_xcd CUs.  On MI355X CU k of an XCD sits in
+ * shader engine k % 4, and workgroups are dealt evenly to the engines that have
+ * a CU enabled: a count that is not a multiple of 4 leaves the engines uneven
+ * and runs like the next lower multiple (6 CUs per XCD measure like 4), so 4
+ * CUs per XCD (32 CUs) is the useful step.
  */
 AG_API ag_status ag_cumask_build(uint32_t* words, int32_t n_words, int32_t total_cus, int32_t n_xcd,
                           int32_t first_cu_per_xcd, int32_t cus_per_xcd);

@@ -58,6 +58,23 @@ def test_granularity_that_does_not_divide_the_device_and_bad_granularity():
             B.Slots(g)
 
 
+def test_finest_granularity_gives_one_entry_per_cu_of_an_xcd():
+    info = B.ag_device_info()
+    n_xcd = info["num_xcd"] or 8
+    per = info["num_cus"] // n_xcd
+    slots = B.Slots(1)
+    try:
+        assert slots.count() == per
+        for i in (0, 2, per - 2, per - 1):
+            e = slots.get(i)
+            assert e["decode_units"] == i + 1
+            assert len(where_it_ran(e["decode_stream"], 2048)) == (i + 1) * n_xcd
+            if i < per - 1:
+                assert len(where_it_ran(e["prefill_stream"], 4096)) == (per - i - 1) * n_xcd
+    finally:
+        slots.close()
+
+
 def test_bind_follows_the_partition_rule_and_later_launches_obey_it():
     info = B.ag_device_info()
     n_xcd = info["num_xcd"] or 8
