@@ -68,7 +68,8 @@ constexpr int kKStages = 3;             // K(t+2) is requested while K(t) is use
 // one 8-wave workgroup per CU.
 constexpr int v_stages(int) { return 2; }
 constexpr int lds_bytes(int nw) { return (kKStages + v_stages(nw)) * kTile; }
-constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may grow before O is rescaled
+constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may exceed m when the ordered path leaves m alone
+constexpr float kWeightSumLimit = 16384.0f;   // a lane's 32 weights of a tile may sum to this much before m is moved
 constexpr float kLog2e = 1.4426950408889634f;
 
 #ifndef AG_PREFILL_WAVES_PER_SIMD
@@ -315,7 +316,6 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
         const bool do_sm = t < wave_tiles, do_pv = t >= 1 && t <= wave_tiles;
         const unsigned char* kb = k_lane + (t % kKStages) * kTile;
         const unsigned char* vb = v_lane + ((t + kVStages - 1) % kVStages) * kTile;   // V(t-1)
-        float mx = -INFINITY;
         if (do_sm) {
             qk_tile(kb, qf, sc);
             if (t >= first_masked) {                 // the tile straddles this wave's diagonal
@@ -328,12 +328,13 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
                         sc[b][i] = key <= qpos ? sc[b][i] : -INFINITY;
                     }
             }
-            mx = row_max(sc) * sl2;                  // scale > 0: max and scaling commute
         }
-        // m is shared by the two lanes of a query, but the test needs no exchange: if either lane's own
-        // maximum outgrew m the whole wave takes the ordered path, which combines the two halves.
-        const bool grow = __builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0;   // uniform over the wave
-        if (do_sm && do_pv && !grow) {
+        // m is a reference, not the running maximum, and the common case does not even look for the tile's
+        // maximum: it takes the weights under the current m and checks afterwards that none came out large
+        // (a lane's sum of 32 weights at most 2^14, so no weight above 2^14; inf and NaN fail the test too).
+        // Only then, and on a wave's first tile, the ordered path finds the row maxima and moves m.
+        bool redo = false;
+        if (do_sm && do_pv) {
             // the common case: two independent pieces, interleaved by hand.  Step i issues the operand read
             // of matrix instruction i + kAhead, matrix instruction i, and the exp of scores 2i and 2i + 1;
             // the fences keep the compiler from regrouping them.  Neighbouring matrix instructions belong
@@ -376,11 +377,15 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
                 if (i + 1 < 16) { x0 = scaled(i + 1, 0); x1 = scaled(i + 1, 1); }
                 __builtin_amdgcn_sched_barrier(0);
             }
-            lsum += psum;
-        } else {
-            if (do_pv) pv_tile(vb, p_prev, o);
+            redo = __builtin_amdgcn_ballot_w64(!(psum <= kWeightSumLimit)) != 0;      // uniform over the wave
+            if (!redo) lsum += psum;
+        }
+        if (!(do_sm && do_pv) || redo) {
+            if (do_pv && !redo) pv_tile(vb, p_prev, o);      // (a redo has done the value product already)
             if (do_sm) {
-                if (grow) {
+                float mx = row_max(sc) * sl2;            // scale > 0: max and scaling commute
+                // m is shared by the two lanes of a query: if either lane's own maximum outgrew m, combine them
+                if (__builtin_amdgcn_ballot_w64(mx > m + kRescaleSlack) != 0) {
                     mx = fmaxf(mx, __shfl_xor(mx, 32));
                     const float m_new = fmaxf(m, mx);    // finite from tile 0 on: key 0 is visible to every row
                     const float alpha = __builtin_amdgcn_exp2f(m - m_new);
