@@ -4,34 +4,34 @@
 // of a session with P cached tokens sees keys 0 .. P + i.  Cold is P = 0.)
 //
 // A dense contraction, bound by the matrix cores: 4 * D flop per visible
-// (query, key) pair and head.  One workgroup (4 waves) owns 128 consecutive
-// query rows of one (session, query head); each wave owns 32 rows and keeps
-// their Q in registers.  Keys and values are taken 64 at a time (4 pages) and
-// staged through LDS:
+// (query, key) pair and head.  One workgroup of NW waves (4 or 8) owns 32 * NW
+// consecutive query rows of one (session, query head); each wave owns 32 rows
+// and keeps their Q in registers.  Keys and values are taken 64 at a time
+// (4 pages) and staged through LDS by direct global-to-LDS loads:
 //
 //   S^T[key][query] = K[key][:] . Q[query][:]      2 x 8 MFMA 32x32x16
-//   softmax weights per query column (running reference m, running sum l, exp2)
+//   softmax weights per query column (reference m, running sum l, exp2)
 //   O^T[d][query]  += V^T[d][key] . P^T[key][query]  4 x 4 MFMA 32x32x16
 //
 // Computing the transposed score tile puts one query in one lane (plus its
 // partner lane + 32), so the row max / sum need a single cross-lane step,
 // and the 8 scores a lane holds for one k-step of the second product are
-// already its B operand: P never leaves registers.  V pages are stored
-// transposed with the slot order the score tile produces, so a value row
-// copies straight into LDS.  LDS rows are padded so 16-byte operand reads
-// are conflict free and every operand address is base + constant.
+// already its B operand: P never leaves registers.  The pools' page layouts
+// are the LDS tile layouts (K chunk-major, V transposed in 8-key chunks in the
+// slot order the score tile produces), so a tile is copied as contiguous runs,
+// 16-byte operand reads are conflict free and every operand address is the
+// lane's base plus a constant.
 //
 // The per-element softmax work on the vector ALUs is about as long as the
-// matrix work (one exp per 512 flop), so the loop is software pipelined to
-// run them side by side inside a wave.  Iteration t of a wave holds three
-// independent pieces
-//        S(t+1) = K(t+1).Q^T   (matrix)      P(t) = exp2(S(t) - m)   (vector)
-//        O     += V(t-1).P(t-1) (matrix)
-// in one basic block.  m is a reference, not the exact running maximum: O is
-// rescaled only when a row's maximum has outgrown m by more than 2^8, which
-// is decided before the block starts and takes a slower, ordered path, as do
-// the tiles that straddle the diagonal (the only ones that need a mask).
-// Tiles wholly above a wave's rows are skipped.
+// matrix work (one exp per 512 flop), so iteration t of a wave interleaves,
+// instruction by instruction, O += V(t-1).P(t-1) (matrix) with
+// P(t) = exp2(S(t) - m) (vector), after S(t) = K(t).Q^T.  m is a reference,
+// not the running maximum: the common case takes the weights under the current
+// m and only checks afterwards that none came out large; a wave's first tile
+// and a failed check take an ordered path that finds the row maxima, rescales
+// O and l when a maximum outgrew m by more than 2^8, and recomputes the weights.
+// Tiles wholly above a wave's rows are skipped; the tiles on the diagonal are
+// masked before the weights are taken.
 //
 // Workgroups are numbered so that the XCD a workgroup lands on (id % 8) owns a
 // contiguous range of KV heads, and inside it session-major, longest query
