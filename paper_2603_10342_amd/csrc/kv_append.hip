@@ -6,10 +6,11 @@
 // to logical position P_s + i -> page bt[s][pos / ps], slot pos % ps.
 //   K page  [D/8][slot][8] : chunk-major; a token's row is cut into 8-channel chunks
 //   V page  [slot/8'][D][8]: transposed in chunks of 8 keys, see v_offset()
-// 16 neighbouring lanes hold 16 consecutive tokens of one chunk of D, so each
-// store instruction writes runs of neighbouring slots.
-// One workgroup of 256 threads takes 16 consecutive rows of the token-major
-// input and one KV head.  HBM-bound: 2 * T * 2*Hkv*D*sizeof bytes (read + write).
+// HBM-bound: 2 * T * 2*Hkv*D*sizeof bytes (read + write).  Two kernels:
+//   kv_append_pages_kernel  page size 16: one workgroup per (touched page, KV head), rows staged in LDS
+//   kv_append_kernel        any page size: one workgroup of 256 threads takes 16 consecutive rows of the
+//                           token-major input and one KV head; 16 neighbouring lanes hold 16 consecutive
+//                           tokens of one chunk of D, so each store instruction writes runs of neighbouring slots.
 #include "ag_internal.h"
 
 namespace ag {
