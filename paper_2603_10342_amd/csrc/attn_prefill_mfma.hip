@@ -103,14 +103,12 @@ __device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&
     auto operand = [&](int i) -> const unsigned char* { return kb + (i & 1) * 512 + (i >> 1) * 2048; };   // (ks, b)
 #pragma unroll
     for (int i = 0; i < kAhead; ++i) opnd[i] = *reinterpret_cast<const bf16x8*>(operand(i));
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sc[b][i] = 0.f;
+    // the first matrix instruction of each key block starts from a literal zero: no accumulator to clear
+    const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         if (i + kAhead < 16) opnd[(i + kAhead) % (kAhead + 1)] = *reinterpret_cast<const bf16x8*>(operand(i + kAhead));
-        sc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], qf[i >> 1], sc[i & 1], 0, 0, 0);
+        sc[i & 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(opnd[i % (kAhead + 1)], qf[i >> 1], i < 2 ? zero : sc[i & 1], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
     }
 }
