@@ -227,6 +227,7 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
     unsigned char* const k_lds = lds;                       // K tile t lives at k_lds + (t % 3) * kTile
     unsigned char* const v_lds = lds + kKStages * kTile;    // V tile t lives at v_lds + (t % kVStages) * kTile
     const int kpg = lane >> 4, kslot = lane & 15;           // K: lane = key of the tile (page, slot)
+    const int kmask[4] = {kpg == 0 ? -1 : 0, kpg == 1 ? -1 : 0, kpg == 2 ? -1 : 0, kpg == 3 ? -1 : 0};
 
     // Physical pages of a tile, through scalar loads (the index is uniform), fetched one iteration before the
     // tile's data is requested, so no data request ever waits for a block-table read.
@@ -239,7 +240,8 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
     };
     // K(tk): instruction i of wave w moves chunk c = kPer*w + i of all 64 keys: four 256-byte runs, one per page.
     auto request_k = [&](int tk, const int (&pid)[4]) {
-        const int mine = kpg == 0 ? pid[0] : kpg == 1 ? pid[1] : kpg == 2 ? pid[2] : pid[3];
+        // this lane's page among the four (uniform) ids, by masks: a chain of ?: here compiles to branches
+        const int mine = (pid[0] & kmask[0]) | (pid[1] & kmask[1]) | (pid[2] & kmask[2]) | (pid[3] & kmask[3]);
         const unsigned char* src = (const unsigned char*)kpool + ((int64_t)mine * hkv + g) * (int64_t)(D * PS * 2) +
                                    (wu * kPer) * 256 + kslot * 16;
         const unsigned dst = lds_address(k_lds) + (tk % kKStages) * kTile + (wu * kPer) * 1024;
