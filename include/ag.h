@@ -141,10 +141,14 @@ AG_API ag_status ag_attn_resume(const ag_kv_cache* cache, const void* q, void* o
  * whose K/V must already be appended, so there is no mask and the result
  * equals the last row of a prefill over the same ctx_lens[s] tokens.
  * ctx_lens[s] = 0 gives a row of zeros.
- * The context is cut into fixed-size splits handled by independent
- * workgroups; their partial (max, sum, weighted values) triples go through
- * `workspace` and are merged in a fixed order, so results are reproducible.
- * workspace_bytes >= ag_attn_decode_workspace_bytes(batch, num_q_heads, head_dim, max_ctx).
+ * The batch's (session, KV head) contexts are laid end to end and cut into
+ * equal shares, one per workgroup (a share may end one context and start
+ * the next); their partial (max, sum, weighted values) triples go through
+ * `workspace`, whose previous contents do not matter, and are merged in a
+ * fixed order, so results are reproducible.
+ * workspace_bytes >= ag_attn_decode_workspace_bytes(batch, num_q_heads, head_dim, max_ctx),
+ * 16-byte aligned.  Calls sharing a workspace must be ordered on one stream.
+ * batch * num_kv_heads * ceil(max_ctx / 32) may not exceed 2^30 (AG_ERR_INVALID_ARG).
  */
 AG_API size_t    ag_attn_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t max_ctx);
 AG_API ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* out,    /* device [B][Hq][D] */

@@ -7,11 +7,19 @@
 // Hq / Hkv flop per byte.  All G = Hq / Hkv query heads that share a KV head
 // are processed together so each byte is fetched once, and the two small
 // contractions run on the matrix cores so that the vector ALUs only do the
-// softmax bookkeeping:
+// softmax bookkeeping.
 //
-//   split kernel, one workgroup (4 waves) per (session, KV head, split).  A session's context is cut into
-//   n = ceil(ctx / split size) equal parts (rounded up to 128 tokens), so no workgroup is left with a sliver;
-//   each wave owns a quarter of a part and walks it 32 tokens (two pages) at a time:
+// Work is dealt in equal shares.  The memory system serves the CUs at about equal rates while all of them
+// stream, so a launch ends when the CU with the most bytes ends: with one workgroup per (session, head, part of
+// the context) the CUs that drew long parts ran up to 45 % over the mean and the step took 112 us where the
+// bytes need 95.  Instead, the (session, KV head) pairs are laid end to end in units of one wave step
+// (32 tokens, two pages), F steps in all, and workgroup w of W takes steps [w q, (w + 1) q) with
+// q = max(8, ceil(F / W)): every workgroup, hence every CU, moves the same number of bytes.  A workgroup's
+// share covers one pair or the end of one and the start of the next (a "segment" each); every workgroup
+// derives the plan itself from the context lengths (a sum and a scan over the batch: the lengths live on
+// the device, and a planning launch ahead of this one would cost more than it saves).
+//
+//   split kernel, per segment: the 4 waves take contiguous quarters and walk them one step at a time:
 //     S^T[token][head] = K[token][:] . Q[head][:]     2 x 4 MFMA 16x16x32 (heads padded to 16)
 //     streaming softmax on S^T (running max m, running sum l; exp2 with log2(e) folded in)
 //     O^T[d][head]    += V^T[d][token] . P^T[token][head]   8 MFMA 16x16x32
@@ -23,10 +31,13 @@
 //   8 scores a lane ends up with are exactly the 8 tokens its V load covers:
 //   no cross-lane shuffles between the products.
 //   The 4 waves are merged in LDS and the workgroup writes one partial
-//   (m, l, O) per query head to the workspace;
+//   (m, l, O) per query head and segment to the workspace;
 //
 //   merge kernel, one workgroup per (session, query head): combines the
-//   partials of all splits in split order (reproducible) and writes bf16.
+//   partials of the pair's segments in order (reproducible) and writes bf16.
+#include <algorithm>
+#include <atomic>
+
 #include "attn_split_common.h"
 
 namespace ag {
@@ -35,196 +46,265 @@ namespace {
 
 using namespace splitk;
 
-// kSteps: steps of 32 tokens a wave may walk; the split size is 128 * kSteps tokens.
-template <int kSteps>
-__global__ __launch_bounds__(256, 2) void decode_split_kernel(AttnArgs a, float* __restrict__ ws_o,
-                                                              float* __restrict__ ws_ml, int n_splits_max)
+constexpr int kMinSteps = kMinSplit / 32;      // a workgroup's share is at least this many steps (256 tokens)
+constexpr int kMaxSteps = 128;                 // and at most this many (the launcher sizes the grid for it)
+
+__device__ __forceinline__ int steps_of(int ctx) { return ctx > 0 ? (ctx + 31) >> 5 : 0; }
+
+// Segments a pair of n steps starting at flat step a may be cut into when shares are q >= kMinSteps steps.
+inline int pieces_max(int max_ctx) { return (((max_ctx + 31) / 32) - 1) / kMinSteps + 2; }
+// Workspace: header [q, then the exclusive step count before each session], partials O, partials (m, l).
+inline size_t header_ints(int batch) { return ((size_t)batch + 1 + 3) & ~(size_t)3; }
+
+__global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_t* __restrict__ hdr,
+                                                              float* __restrict__ ws_o, float* __restrict__ ws_ml,
+                                                              int pmax)
 {
-    static_assert(kSteps >= 1 && kSteps <= 16, "a wave walks 1..16 steps of 32 tokens");
-    constexpr int kSplit = 128 * kSteps;
     __shared__ float s_o[4][16][D];     // per wave, per (padded) head: unnormalised O
     __shared__ float s_m[4][16];
     __shared__ float s_l[4][16];
+    __shared__ int s_red[4];
+    constexpr int kQRow = 2 * D + 16;
+    __shared__ __attribute__((aligned(16))) unsigned char s_q[16 * kQRow];
+    __shared__ int s_start[2];          // session holding the workgroup's first step, steps before that session
 
-    // Workgroups are dealt to the 8 XCDs round-robin in linear order (x fastest).  Short sessions only have
-    // the low split numbers, so if blockIdx.x were the split itself the XCDs that draw the low numbers would
-    // get all the work of short sessions on top of their share of long ones (with 8 splits: everything on
-    // one XCD per split).  Rotating the split by head and session spreads them evenly.
-    const int g = blockIdx.y, s = blockIdx.z;
-    const int split = (int)((blockIdx.x + blockIdx.y + blockIdx.z) % gridDim.x);
-    const int ctx = a.ctx_lens[s];
-    if (ctx <= 0) return;
-    const int part = part_tokens(ctx, kSplit);
-    const int start = split * part;
-    if (start >= ctx) return;            // uniform over the workgroup
-    const int wave_tok = part >> 2;      // a multiple of 32, at most 32 * kSteps
-
-    const int hkv = a.c.hkv, hq = a.hq;
+    const int B = a.batch, hkv = a.c.hkv, hq = a.hq;
     const int G = hq / hkv;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int r = lane & 15, c = lane >> 4;
-    const int wstart = start + w * wave_tok;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wg = blockIdx.x, W = gridDim.x;
+
+    // ---- the plan: F, q and where this workgroup's share starts ----
+    int total;
+    {
+        int loc = 0;
+        for (int s = tid; s < B; s += 256) loc += steps_of(a.ctx_lens[s]);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) loc += __shfl_xor(loc, d);
+        if (lane == 0) s_red[w] = loc;
+        __syncthreads();
+        total = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+        __syncthreads();
+    }
+    const int F = hkv * total;
+    if (F == 0) return;
+    const int q = max(kMinSteps, (F + W - 1) / W);
+    const int f0 = wg * q;              // q <= kMaxSteps by the launcher's choice of W: no overflow
+    if (wg == 0 && tid == 0) hdr[0] = q;
+    if (f0 >= F) return;                // uniform over the workgroup
+    const int f1 = min(f0 + q, F);
+    {
+        int carry = 0;                  // steps of the sessions before this chunk of 256
+        for (int s0 = 0; s0 < B; s0 += 256) {
+            const int s = s0 + tid;
+            const int n = s < B ? steps_of(a.ctx_lens[s]) : 0;
+            int incl = n;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(incl, d);
+                if (lane >= d) incl += t;
+            }
+            if (lane == 63) s_red[w] = incl;
+            __syncthreads();
+            int woff = 0;
+            for (int ww = 0; ww < w; ++ww) woff += s_red[ww];
+            const int chunk = s_red[0] + s_red[1] + s_red[2] + s_red[3];
+            const int excl = carry + woff + incl - n;
+            if (n > 0 && hkv * excl <= f0 && f0 < hkv * (excl + n)) { s_start[0] = s; s_start[1] = excl; }
+            if (wg == 0 && s < B) hdr[1 + s] = excl;       // workgroup 0 publishes the plan for the merge kernel
+            __syncthreads();
+            carry += chunk;
+            if (wg != 0 && hkv * carry > f0) break;         // found (uniform); workgroup 0 goes on publishing
+        }
+    }
+    int s = s_start[0];
+    int base = hkv * s_start[1];        // flat step at which session s starts
+    int ctx = a.ctx_lens[s];
+    int n = steps_of(ctx);
+    int g = (f0 - base) / n;
+    int u = (f0 - base) - g * n;        // first step inside (s, g)
 
     const __bf16* kpool = (const __bf16*)a.c.k;
     const __bf16* vpool = (const __bf16*)a.c.v;
-
-    // Q^T as the B operand: column = head r (zero beyond G), k = channels kk*32 + c*8 .. +7
-    bf16x8 qf[4];
-    {
-        const __bf16* qrow = (const __bf16*)a.q + ((int64_t)s * hq + (int64_t)g * G + (r < G ? r : 0)) * D + c * 8;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 x = ld16(qrow + kk * 32);
-            if (r >= G) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            qf[kk] = x;
-        }
-    }
-
-    // physical pages of this wave's logical pages (clamped to the session's last page)
-    const int n_pages_ctx = (ctx + PS - 1) >> 4;
-    int my_pid;
-    {
-        const int lp = min((wstart >> 4) + (lane & (2 * kSteps - 1)), n_pages_ctx - 1);
-        my_pid = a.bt[(int64_t)s * a.max_pages + lp];
-    }
-    const int n_steps = wstart < ctx ? min(wave_tok >> 5, (ctx - wstart + 31) >> 5) : 0;   // uniform over the wave
-
     const float sl2 = a.scale * kLog2e;
-    float m = -INFINITY, lsum = 0.0f;
-    f32x4 o[8];
-#pragma unroll
-    for (int mb = 0; mb < 8; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Row r of the first score product is slot (r & 7) of page (r >> 3) of the step; the second product takes
-    // slots 8..15.  K page layout [chunk][slot][8]: lanes r = 0..7 of one lane group read 128 contiguous bytes.
-    // Lane group c then owns slots (c&1)*4 + {0..3} and 8 + (c&1)*4 + {0..3} of page (c >> 1): exactly the 8
-    // keys of chunk (c&1) of that value page (see v_offset), so its 16-byte V load is its P operand's partner.
-    const int k_pg = r >> 3;
-    const int k_off = (c * PS + (r & 7)) * 8;            // + kk * 4 * PS * 8 per k-step; + 8 * 8 for slots 8..15
-    const int v_pg = c >> 1;
-    const int v_off = ((c & 1) * D + r) * 8;             // value page [half][channel][8 keys]; + mb * 16 * 8 per block
+    for (int f = f0; f < f1 && s < B;) {                 // one segment per pass; every value here is uniform
+        const int k = min(n - u, f1 - f);                // steps of this segment, 1 .. q
+        const int per = (k + 3) >> 2;                    // steps per wave, at most kMaxSteps / 4 = 32
+        const int my_u = u + w * per;
+        const int my_n = max(0, min(per, k - w * per));
 
-    auto load_step = [&](int st, StepRegs& x) {
-        const int64_t pA = __builtin_amdgcn_readlane(my_pid, 2 * st);
-        const int64_t pB = __builtin_amdgcn_readlane(my_pid, 2 * st + 1);
-        const __bf16* kp = kpool + ((k_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + k_off;
-        const __bf16* vp = vpool + ((v_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + v_off;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            x.k1[kk] = ld16_stream(kp + kk * 4 * PS * 8);
-            x.k2[kk] = ld16_stream(kp + kk * 4 * PS * 8 + 64);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16_stream(vp + mb * 16 * 8);
-    };
+        // Everything a lane derives from its number is derived again in each segment, behind a barrier the
+        // compiler cannot see through: hoisted out of this loop those values would stay in registers across
+        // the step loop, which needs all 128 for the 16 loads of a step to be in flight together.
+        int lane_s = lane;
+        asm volatile("" : "+v"(lane_s));
+        const int r = lane_s & 15, c = lane_s >> 4;
+        // Row r of the first score product is slot (r & 7) of page (r >> 3) of the step; the second product takes
+        // slots 8..15.  K page layout [chunk][slot][8]: lanes r = 0..7 of one lane group read 128 contiguous bytes.
+        // Lane group c then owns slots (c&1)*4 + {0..3} and 8 + (c&1)*4 + {0..3} of page (c >> 1): exactly the 8
+        // keys of chunk (c&1) of that value page (see v_offset), so its 16-byte V load is its P operand's partner.
+        const int k_pg = r >> 3;
+        const int k_off = (c * PS + (r & 7)) * 8;            // + kk * 4 * PS * 8 per k-step; + 8 * 8 for slots 8..15
+        const int v_pg = c >> 1;
+        const int v_off = ((c & 1) * D + r) * 8;             // value page [half][channel][8 keys]; + mb * 16 * 8 per block
 
-    auto compute_step = [&](int st, StepRegs& x) {
-        const int tok0 = wstart + st * 32;
-        f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qf[kk], s1, 0, 0, 0);
-            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qf[kk], s2, 0, 0, 0);
+        // Q of the pair's G heads goes through LDS (rows of 256 B + 16 B of padding, zero beyond G): as the B
+        // operand, column = head r, k = channels kk*32 + c*8 .. +7, read when a step needs it rather than
+        // held in 16 registers across the loads
+        {
+            int tid_q = tid;                                 // 256 threads: 16 heads x 16 pieces of 16 bytes
+            asm volatile("" : "+v"(tid_q));
+            const int head = tid_q >> 4, ch = tid_q & 15;
+            u32x4 x = {0, 0, 0, 0};
+            if (head < G)
+                x = *reinterpret_cast<const u32x4*>((const __bf16*)a.q + ((int64_t)s * hq + (int64_t)g * G + head) * D + ch * 8);
+            *reinterpret_cast<u32x4*>(s_q + head * kQRow + ch * 16) = x;
         }
-        // s1[i]: token tokb + i, s2[i]: token tokb + 8 + i, of head r
-        const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
-        const int keep = ctx - tokb;     // token tokb + j exists iff j < keep
-        float xs[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
-            xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
+        // physical pages of this wave's steps (lane i: page i of its run, clamped to the session's last page)
+        int my_pid = 0;
+        if (my_n > 0) {
+            const int lp = min(2 * my_u + lane_s, ((ctx + PS - 1) >> 4) - 1);
+            my_pid = a.bt[(int64_t)s * a.max_pages + lp];
         }
-        float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m, mx);          // finite: token tok0 exists
-        const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-        float psum = 0.f;
-        bf16x8 pb;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float p = __builtin_amdgcn_exp2f(xs[e] - m_new);
-            psum += p;
-            pb[e] = (__bf16)p;
-        }
-        lsum = lsum * alpha + psum;
-        m = m_new;
-        if (tok0 + 32 > ctx) {           // last, partial step: unwritten slots may hold anything, NaN included
-#pragma unroll
-            for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep, keep - 8);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb) {
-            o[mb] *= alpha;
-            o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[mb], 0, 0, 0);
-        }
-    };
 
-#if AG_DECODE_PREFETCH
-    StepRegs buf[2];
-    if (n_steps > 0) load_step(0, buf[0]);
+        float m = -INFINITY, lsum = 0.0f;
+        f32x4 o[8];
 #pragma unroll
-    for (int st = 0; st < kSteps; ++st) {
-        if (st < n_steps) {
-            if (st + 1 < kSteps && st + 1 < n_steps) load_step(st + 1, buf[(st + 1) & 1]);
-            compute_step(st, buf[st & 1]);
-        }
-    }
-#else
-#pragma unroll
-    for (int st = 0; st < kSteps; ++st) {
-        if (st < n_steps) {
+        for (int mb = 0; mb < 8; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+        __syncthreads();                                 // Q is in LDS
+        const unsigned char* q_lane = s_q + r * kQRow + c * 16;
+
+#pragma unroll 1
+        for (int st = 0; st < my_n; ++st) {
             StepRegs x;
-            load_step(st, x);
-            compute_step(st, x);
+            {
+                const int64_t pA = __builtin_amdgcn_readlane(my_pid, 2 * st);
+                const int64_t pB = __builtin_amdgcn_readlane(my_pid, 2 * st + 1);
+                const __bf16* kp = kpool + ((k_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + k_off;
+                const __bf16* vp = vpool + ((v_pg ? pB : pA) * hkv + g) * (int64_t)(D * PS) + v_off;
+#pragma unroll
+                for (int kk = 0; kk < 4; ++kk) {
+                    x.k1[kk] = ld16_stream(kp + kk * 4 * PS * 8);
+                    x.k2[kk] = ld16_stream(kp + kk * 4 * PS * 8 + 64);
+                }
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16_stream(vp + mb * 16 * 8);
+                // all 16 loads are in flight before anything waits: left to itself the scheduler starts the
+                // score product on the first keys and issues the value loads a memory latency later
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const int tok0 = (my_u + st) * 32;
+            f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                const bf16x8 qk = *reinterpret_cast<const bf16x8*>(q_lane + kk * 64);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qk, s1, 0, 0, 0);
+                s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qk, s2, 0, 0, 0);
+            }
+            // s1[i]: token tokb + i, s2[i]: token tokb + 8 + i, of head r
+            const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
+            const int keep = ctx - tokb;     // token tokb + j exists iff j < keep
+            float xs[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
+                xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx);          // finite: token tok0 exists
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            float psum = 0.f;
+            bf16x8 pb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float p = __builtin_amdgcn_exp2f(xs[e] - m_new);
+                psum += p;
+                pb[e] = (__bf16)p;
+            }
+            lsum = lsum * alpha + psum;
+            m = m_new;
+            if (tok0 + 32 > ctx) {           // last, partial step: unwritten slots may hold anything, NaN included
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep, keep - 8);
+            }
+#pragma unroll
+            for (int mb = 0; mb < 8; ++mb) {
+                o[mb] *= alpha;
+                o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[mb], 0, 0, 0);
+            }
         }
-    }
-#endif
-    lsum += __shfl_xor(lsum, 16);
-    lsum += __shfl_xor(lsum, 32);
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
 
-    // o[mb][i] is O^T[d = mb*16 + c*4 + i][head r]
+        // o[mb][i] is O^T[d = mb*16 + c*4 + i][head r]
+        int lane_e = lane, tid_e = tid;                  // (as above: addresses of the merge are computed here)
+        asm volatile("" : "+v"(lane_e), "+v"(tid_e));
+        const int re = lane_e & 15, ce = lane_e >> 4;
 #pragma unroll
-    for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(&s_o[w][r][mb * 16 + c * 4]) = o[mb];
-    if (c == 0) { s_m[w][r] = m; s_l[w][r] = lsum; }
-    __syncthreads();
+        for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(&s_o[w][re][mb * 16 + ce * 4]) = o[mb];
+        if (ce == 0) { s_m[w][re] = m; s_l[w][re] = lsum; }
+        __syncthreads();
 
-    for (int idx = threadIdx.x; idx < G * D; idx += 256) {
-        const int head = idx >> 7, d = idx & (D - 1);
-        float ms = s_m[0][head];
+        // the pair starts at flat step base + g n; its segments are numbered from the workgroup holding that step
+        const int piece = wg - (base + g * n) / q;
+        if (piece < pmax) {
+            for (int idx = tid_e; idx < G * D; idx += 256) {
+                const int head = idx >> 7, d = idx & (D - 1);
+                float ms = s_m[0][head];               // wave 0 always has a step: finite
 #pragma unroll
-        for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][head]);
-        float acc = 0.f, l = 0.f;
+                for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][head]);
+                float acc = 0.f, l = 0.f;
 #pragma unroll
-        for (int ww = 0; ww < 4; ++ww) {
-            const float f = exp2f(s_m[ww][head] - ms);   // a wave without tokens has m = -inf -> 0
-            acc += f * s_o[ww][head][d];
-            l += f * s_l[ww][head];
+                for (int ww = 0; ww < 4; ++ww) {
+                    const float fw = exp2f(s_m[ww][head] - ms);   // a wave without steps has m = -inf -> 0
+                    acc += fw * s_o[ww][head][d];
+                    l += fw * s_l[ww][head];
+                }
+                const int64_t slot = ((int64_t)s * hq + (int64_t)g * G + head) * pmax + piece;
+                ws_o[slot * D + d] = acc;
+                if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = l; }
+            }
         }
-        const int64_t slot = ((int64_t)s * hq + (int64_t)g * G + head) * n_splits_max + split;
-        ws_o[slot * D + d] = acc;
-        if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = l; }
+        __syncthreads();                                 // s_o is rewritten by the next segment
+
+        f += k;
+        u += k;
+        if (u == n) {                                    // on to the next pair
+            u = 0;
+            if (++g == hkv) {
+                g = 0;
+                base += hkv * n;
+                do {
+                    ++s;
+                    ctx = s < B ? a.ctx_lens[s] : 0;
+                    n = steps_of(ctx);
+                } while (s < B && n == 0);
+            }
+        }
     }
 }
 
-__global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const float* __restrict__ ws_o,
-                                                           const float* __restrict__ ws_ml, int n_splits_max,
-                                                           int split_tokens)
+__global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const int32_t* __restrict__ hdr,
+                                                           const float* __restrict__ ws_o,
+                                                           const float* __restrict__ ws_ml, int pmax)
 {
     const int row = blockIdx.x;                 // s * hq + h
-    const int s = row / a.hq;
+    const int s = row / a.hq, h = row - s * a.hq;
     const int d = threadIdx.x;
     const int ctx = a.ctx_lens[s];
     __bf16* out = (__bf16*)a.out + (int64_t)row * D;
     if (ctx <= 0) { out[d] = (__bf16)0.0f; return; }
-    const int part = part_tokens(ctx, split_tokens);
-    const int n = (ctx + part - 1) / part;               // parts that exist, as the split kernel cuts them
-    const int64_t base = (int64_t)row * n_splits_max;
+    const int q = max(1, hdr[0]), n = steps_of(ctx);
+    const int first = a.c.hkv * hdr[1 + s] + (h / (a.hq / a.c.hkv)) * n;       // the pair's first flat step
+    const int pieces = min(pmax, (first + n - 1) / q - first / q + 1);          // as the split kernel cuts them
+    const int64_t base = (int64_t)row * pmax;
     float ms = -INFINITY;
-    for (int i = 0; i < n; ++i) ms = fmaxf(ms, ws_ml[(base + i) * 2]);
+    for (int i = 0; i < pieces; ++i) ms = fmaxf(ms, ws_ml[(base + i) * 2]);
     float acc = 0.f, l = 0.f;
-    for (int i = 0; i < n; ++i) {               // fixed order: reproducible
+    for (int i = 0; i < pieces; ++i) {          // fixed order: reproducible
         const float f = exp2f(ws_ml[(base + i) * 2] - ms);
         acc += f * ws_o[(base + i) * D + d];
         l += f * ws_ml[(base + i) * 2 + 1];
@@ -232,23 +312,29 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const flo
     out[d] = (__bf16)(acc / l);
 }
 
-// Split size for a launch: as long as possible (each workgroup pays a fixed start-up of three dependent reads)
-// while the launch still has a few workgroups per CU to balance with.  Only host-known bounds are available.
-inline int choose_split(int batch, int hkv, int max_ctx)
+// Workgroup slots of the current device: 4 workgroups of 256 threads per CU at this kernel's register count.
+int device_slots()
 {
-    const int64_t want = 4 * 256;            // workgroups, counting sessions at about 60 % of max_ctx
-    for (int split = 2048; split > kMinSplit; split >>= 1) {
-        const int64_t wgs = (int64_t)batch * hkv * ((6 * (int64_t)max_ctx / 10 + split - 1) / split);
-        if (wgs >= want) return split;
+    static std::atomic<int> cached[16];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); return 1024; }
+    const bool in_table = dev >= 0 && dev < 16;
+    if (in_table) { const int v = cached[dev].load(); if (v > 0) return v; }
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        cus = 256;
     }
-    return kMinSplit;
+    if (in_table) cached[dev].store(4 * cus);
+    return 4 * cus;
 }
 
 }  // namespace
 
 size_t decode_workspace_bytes(int batch, int hq, int d, int max_ctx)
 {
-    return (size_t)batch * hq * splits_for(max_ctx, kMinSplit) * (size_t)(d + 2) * sizeof(float);
+    if (batch <= 0) return 0;
+    return header_ints(batch) * sizeof(int32_t) + (size_t)batch * hq * pieces_max(max_ctx) * (size_t)(d + 2) * sizeof(float);
 }
 
 bool decode_mfma_supported(const AttnArgs& a)
@@ -259,29 +345,23 @@ bool decode_mfma_supported(const AttnArgs& a)
 
 ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
-#ifdef AG_DECODE_FORCE_SPLIT
-    const int split = AG_DECODE_FORCE_SPLIT;
-#else
-    const int split = choose_split(a.batch, a.c.hkv, a.max_ctx);
-#endif
-    const int nsm = splits_for(a.max_ctx, split);
-    float* ws_o = (float*)ws;
-    float* ws_ml = ws_o + (size_t)a.batch * a.hq * nsm * D;
-    if (a.batch > 65535 || a.c.hkv > 65535) { set_error("batch or KV heads beyond one launch grid"); return AG_ERR_INVALID_ARG; }
+    const int pmax = pieces_max(a.max_ctx);
+    int32_t* hdr = (int32_t*)ws;
+    float* ws_o = (float*)(hdr + header_ints(a.batch));
+    float* ws_ml = ws_o + (size_t)a.batch * a.hq * pmax * D;
+    // Upper bound of the step count from the host-known bounds; the grid is sized so that a share is at most
+    // kMaxSteps steps even if every session is max_ctx long, and is never smaller than the device's slots.
+    const int64_t f_max = (int64_t)a.c.hkv * a.batch * ((a.max_ctx + 31) / 32);
+    if (f_max > (1 << 30)) { set_error("decode batch of %lld steps of 32 tokens is beyond one launch", (long long)f_max); return AG_ERR_INVALID_ARG; }
     if (a.max_ctx > 0) {
-        const dim3 grid(nsm, a.c.hkv, a.batch);
+        const int grid = (int)std::max<int64_t>(device_slots(), (f_max + kMaxSteps - 1) / kMaxSteps);
         prof_before(st);
-        switch (split) {
-            case 2048: hipLaunchKernelGGL(decode_split_kernel<16>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
-            case 1024: hipLaunchKernelGGL(decode_split_kernel<8>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
-            case 512:  hipLaunchKernelGGL(decode_split_kernel<4>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
-            default:   hipLaunchKernelGGL(decode_split_kernel<2>, grid, dim3(256), 0, st, a, ws_o, ws_ml, nsm); break;
-        }
+        hipLaunchKernelGGL(decode_split_kernel, dim3(grid), dim3(256), 0, st, a, hdr, ws_o, ws_ml, pmax);
         prof_after(st);
         ag_status e = hip_check(hipGetLastError(), "decode split launch");
         if (e) return e;
     }
-    hipLaunchKernelGGL(decode_merge_kernel, dim3(a.batch * a.hq), dim3(128), 0, st, a, ws_o, ws_ml, nsm, split);
+    hipLaunchKernelGGL(decode_merge_kernel, dim3(a.batch * a.hq), dim3(128), 0, st, a, hdr, ws_o, ws_ml, pmax);
     return hip_check(hipGetLastError(), "decode merge launch");
 }
 

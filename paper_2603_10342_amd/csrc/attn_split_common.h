@@ -13,9 +13,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int D = 128;
 constexpr int PS = 16;
-#ifndef AG_DECODE_PREFETCH
-#define AG_DECODE_PREFETCH 0
-#endif
 
 // Tokens of one part of a session's context when it is cut for splits of at most `split` tokens:
 // n = ceil(ctx / split) equal parts, each a multiple of 128 (32 per wave step x 4 waves).

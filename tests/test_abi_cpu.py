@@ -57,9 +57,11 @@ def test_null_and_shape_errors_come_from_the_host_layer():
 
 
 def test_decode_workspace_size():
-    # one (max, sum, D values) fp32 triple per (session, query head, split), sized for the smallest split (256)
-    assert B.ag_attn_decode_workspace_bytes(64, 32, 128, 4096) == 64 * 32 * 16 * 130 * 4
-    assert B.ag_attn_decode_workspace_bytes(2, 4, 64, 1) == 2 * 4 * 1 * 66 * 4
+    # a header of 1 + batch int32 (rounded up to 16 bytes), then one (max, sum, D values) fp32 triple per
+    # (session, query head, segment): shares are at least 256 tokens, and a context of n shares can straddle
+    # one more boundary than it has shares
+    assert B.ag_attn_decode_workspace_bytes(64, 32, 128, 4096) == 68 * 4 + 64 * 32 * 17 * 130 * 4
+    assert B.ag_attn_decode_workspace_bytes(2, 4, 64, 1) == 4 * 4 + 2 * 4 * 2 * 66 * 4
     assert B.ag_attn_decode_workspace_bytes(0, 4, 64, 1) == 0
 
 

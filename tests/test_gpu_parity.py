@@ -156,6 +156,63 @@ def test_decode_names_the_planted_position():
             assert named == tg[s][h], (s, h, named, tg[s][h])
 
 
+def _decode_against_oracle(g, ctx, seed, max_ctx=None, pad_pages=0, ws_fill=None):
+    """Fill every session's whole context, then decode with fresh queries; sessions of length 0 must give zeros."""
+    ctx = np.asarray(ctx, np.int32)
+    bt = I.deal_block_tables(I.rng_for(seed, 0), np.maximum(ctx, 1), 16, g.num_pages)
+    if pad_pages > bt.shape[1]:
+        bt = np.concatenate([bt, np.zeros((bt.shape[0], pad_pages - bt.shape[1]), np.int32)], axis=1)
+    fill = make_batch(g, np.zeros_like(ctx), ctx, seed=seed, bt=bt, sigma_qk=1.0, sigma_v=1.0)
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    d = DevBatch(fill)
+    gpu_append(cache, d)
+    oracle_append(kp, vp, fill)
+    qn = I.normal_values(seed, 9, 0, (len(ctx), g.num_q_heads, g.head_dim), 1.0, g.dtype)
+    max_ctx = int(ctx.max()) if max_ctx is None else max_ctx
+    q = to_dev(qn, g.dtype)
+    if ws_fill is None:
+        got = gpu_decode(cache, q, d.bt, i32(ctx), max_ctx, g)
+    else:
+        nbytes = B.ag_attn_decode_workspace_bytes(len(ctx), g.num_q_heads, g.head_dim, max_ctx)
+        ws = torch.full((nbytes // 4,), ws_fill, dtype=torch.float32, device="cuda")
+        out = torch.full_like(q, float("nan"))
+        B.ag_attn_decode(cache, q, out, d.bt, i32(ctx), max_ctx, g.num_q_heads, g.scale, ws)
+        torch.cuda.synchronize()
+        from gpu_helpers import to_f64
+        got = to_f64(out, g.dtype)
+    live = np.nonzero(ctx > 0)[0]
+    assert np.all(got[ctx == 0] == 0)
+    ref = O.decode(kp, vp, g.dtype, qn[live], bt[live], ctx[live], g.num_q_heads, g.scale)
+    check_close(got[live], ref, g.dtype, "decode")
+
+
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 1)])
+def test_decode_shares_that_span_many_short_sessions(hq, hkv):
+    """300 sessions of 0..200 tokens: more sessions than one pass of the plan's scan covers, and every
+    workgroup's share (at least 8 steps of 32 tokens) runs over several (session, head) pairs, some empty."""
+    g = slm(pages=2600, hq=hq, hkv=hkv)
+    rng = np.random.default_rng(41)
+    ctx = rng.integers(1, 201, size=300)
+    ctx[rng.integers(0, 300, size=40)] = 0
+    ctx[[0, 255, 256, 299]] = [0, 33, 0, 1]            # empty sessions at the ends of the scan's passes
+    _decode_against_oracle(g, ctx, seed=41)
+
+
+def test_decode_bounds_far_above_the_lengths():
+    """max_ctx (which sizes the grid and the workspace) 100x the longest context, on a dirty workspace."""
+    g = slm(pages=600)
+    _decode_against_oracle(g, [300, 17, 0, 1024, 95], seed=42, max_ctx=32768, pad_pages=2048, ws_fill=float("nan"))
+    _decode_against_oracle(g, [300, 17, 0, 1024, 95], seed=42, max_ctx=32768, pad_pages=2048, ws_fill=1e30)
+
+
+def test_decode_one_share_per_workgroup_boundaries():
+    """Lengths chosen so that shares end exactly on, one step before and one step after a pair's end."""
+    g = slm(pages=4200, hq=8, hkv=2)
+    # 1024 workgroup slots: F = 2 * sum(steps); with these lengths q = 8 steps and pairs of 8, 16, 9, 7, 17 steps
+    _decode_against_oracle(g, [256, 512, 288, 224, 544, 8192 + 31, 8192], seed=43)
+
+
 def test_decode_is_reproducible_and_ignores_stale_workspace():
     g = slm(pages=512)
     c = I.make_decode(batch=6, lo=100, hi=1200, num_pages=512, geom=g, seed=9)
@@ -329,8 +386,8 @@ def test_decode_with_more_than_16_heads_per_kv_head_uses_the_general_kernel():
     check_close(got, ref, g.dtype, "decode G=32")
 
 
-def test_long_context_decode_uses_the_longest_split():
-    """One session of 40000 tokens: 2048-token splits, many partials to merge, page ids far apart."""
+def test_long_context_decode_many_partials():
+    """One session of 40000 tokens: cut into the shortest shares (157 partials per head), page ids far apart."""
     g = slm(pages=2600, hq=8, hkv=2)
     ctx = np.array([40000, 129], np.int32)
     bt = I.deal_block_tables(I.rng_for(31, 0), ctx, 16, g.num_pages)
