@@ -4,6 +4,8 @@ import ctypes as C
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from paper_2603_10342_amd import binding as B
@@ -89,3 +91,32 @@ def test_empty_mask_is_rejected_without_touching_the_device():
     assert l.ag_stream_create_cumask(C.byref(out), words, 8) == B.AG_ERR_INVALID_ARG
     assert l.ag_stream_create_cumask(None, words, 8) == B.AG_ERR_INVALID_ARG
     assert l.ag_stream_destroy(None) == B.AG_ERR_INVALID_ARG
+
+
+def test_decode_workspace_covers_every_cut_of_a_context():
+    """The decode kernel deals the batch's (session, KV head) contexts, laid end to end in steps of 32 tokens,
+    in equal shares of q >= 8 steps; a context of n steps starting at flat step a is then cut into
+    floor((a + n - 1) / q) - floor(a / q) + 1 partials.  The workspace must hold that many per (session, head)
+    for any batch the bounds admit: checked here on the host against the size function."""
+    rng = np.random.default_rng(7)
+    for trial in range(200):
+        batch = int(rng.integers(1, 40))
+        hkv = int(rng.choice([1, 2, 4, 8]))
+        hq = hkv * int(rng.choice([1, 2, 4]))
+        max_ctx = int(rng.integers(1, 20000))
+        ctx = rng.integers(0, max_ctx + 1, size=batch)
+        ctx[rng.integers(0, batch)] = max_ctx
+        nbytes = B.ag_attn_decode_workspace_bytes(batch, hq, 128, max_ctx)
+        header = ((batch + 1 + 3) // 4) * 4 * 4
+        slots = (nbytes - header) // (batch * hq * 130 * 4)
+        assert header + batch * hq * slots * 130 * 4 == nbytes
+        steps = (ctx + 31) // 32
+        F = hkv * int(steps.sum())
+        for W in (1024, 1, 37, max(1024, (hkv * batch * ((max_ctx + 31) // 32) + 127) // 128)):
+            q = max(8, -(-F // W))
+            a = 0
+            for n in steps:
+                for g in range(hkv):
+                    if n:
+                        assert (a + n - 1) // q - a // q + 1 <= slots, (batch, hkv, max_ctx, W, q, a, n, slots)
+                    a += int(n)
