@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
     __shared__ int s_red[4];
     constexpr int kQRow = 2 * D + 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_q[16 * kQRow];
-    __shared__ int s_start[2];          // session holding the workgroup's first step, steps before that session
+    __shared__ int s_start[3];          // session holding the workgroup's first step, steps before it, its length
 
     const int B = a.batch, hkv = a.c.hkv, hq = a.hq;
     const int G = hq / hkv;
@@ -97,7 +97,8 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
         int carry = 0;                  // steps of the sessions before this chunk of 256
         for (int s0 = 0; s0 < B; s0 += 256) {
             const int s = s0 + tid;
-            const int n = s < B ? steps_of(a.ctx_lens[s]) : 0;
+            const int len = s < B ? a.ctx_lens[s] : 0;
+            const int n = steps_of(len);
             int incl = n;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
@@ -110,7 +111,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
             for (int ww = 0; ww < w; ++ww) woff += s_red[ww];
             const int chunk = s_red[0] + s_red[1] + s_red[2] + s_red[3];
             const int excl = carry + woff + incl - n;
-            if (n > 0 && hkv * excl <= f0 && f0 < hkv * (excl + n)) { s_start[0] = s; s_start[1] = excl; }
+            if (n > 0 && hkv * excl <= f0 && f0 < hkv * (excl + n)) { s_start[0] = s; s_start[1] = excl; s_start[2] = len; }
             if (wg == 0 && s < B) hdr[1 + s] = excl;       // workgroup 0 publishes the plan for the merge kernel
             __syncthreads();
             carry += chunk;
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
     }
     int s = s_start[0];
     int base = hkv * s_start[1];        // flat step at which session s starts
-    int ctx = a.ctx_lens[s];
+    int ctx = s_start[2];
     int n = steps_of(ctx);
     int g = (f0 - base) / n;
     int u = (f0 - base) - g * n;        // first step inside (s, g)
