@@ -301,16 +301,7 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const int
     const int q = max(1, hdr[0]), n = steps_of(ctx);
     const int first = a.c.hkv * hdr[1 + s] + (h / (a.hq / a.c.hkv)) * n;       // the pair's first flat step
     const int pieces = min(pmax, (first + n - 1) / q - first / q + 1);          // as the split kernel cuts them
-    const int64_t base = (int64_t)row * pmax;
-    float ms = -INFINITY;
-    for (int i = 0; i < pieces; ++i) ms = fmaxf(ms, ws_ml[(base + i) * 2]);
-    float acc = 0.f, l = 0.f;
-    for (int i = 0; i < pieces; ++i) {          // fixed order: reproducible
-        const float f = exp2f(ws_ml[(base + i) * 2] - ms);
-        acc += f * ws_o[(base + i) * D + d];
-        l += f * ws_ml[(base + i) * 2 + 1];
-    }
-    out[d] = (__bf16)(acc / l);
+    out[d] = (__bf16)merge_partials(ws_o, ws_ml, (int64_t)row * pmax, pieces, d);
 }
 
 // CUs of the current device.

@@ -39,7 +39,8 @@ using namespace splitk;
 enum { kKeysItem = 0, kRowsItem = 1 };
 
 // plan[0] = number of items; item i is plan[4 + 4i ..]: session, first row (within the session's chunk), rows, kind.
-// row_item[row] = the item that holds query row `row`.
+// row_ctx[row] = keys the item that holds query row `row` was cut over: prefix + rows of the chunk up to the
+// item's last (what the merge kernel needs to count the row's partials, without walking plan -> session -> prefix).
 // rk: rows of a full keys item; rw: rows of a full rows item, 0 if the launch has no rows items.
 __device__ __forceinline__ int items_of(int n, int rk, int rw)
 {
@@ -48,10 +49,11 @@ __device__ __forceinline__ int items_of(int n, int rk, int rw)
 }
 
 __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restrict__ new_lens,
+                                                          const int32_t* __restrict__ prefix_lens,
                                                           const int32_t* __restrict__ cu_new, int batch,
                                                           int total_rows, int rk, int rw,
                                                           int32_t* __restrict__ plan,
-                                                          int32_t* __restrict__ row_item)
+                                                          int32_t* __restrict__ row_ctx)
 {
     __shared__ int scan[256];
     __shared__ int carry;
@@ -60,6 +62,7 @@ __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restr
     for (int base = 0; base < batch; base += 256) {
         const int s = base + threadIdx.x;
         const int n = s < batch ? new_lens[s] : 0;
+        const int P = (s < batch && prefix_lens) ? prefix_lens[s] : 0;
         const int mine = items_of(n, rk, rw);
         scan[threadIdx.x] = mine;
         __syncthreads();
@@ -78,7 +81,7 @@ __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restr
             e[0] = s; e[1] = t0; e[2] = nt;
             e[3] = (rw && nt > rk) ? kRowsItem : kKeysItem;
             const int row0 = cu_new[s] + t0;
-            for (int x = 0; x < nt && row0 + x < total_rows; ++x) row_item[row0 + x] = first + i;
+            for (int x = 0; x < nt && row0 + x < total_rows; ++x) row_ctx[row0 + x] = P + t0 + nt;
         }
         __syncthreads();
         if (threadIdx.x == 255) carry += scan[255];
@@ -460,28 +463,16 @@ __global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnA
 
 __global__ __launch_bounds__(128) void merged_merge_kernel(AttnArgs a, const float* __restrict__ ws_o,
                                                            const float* __restrict__ ws_ml,
-                                                           const int32_t* __restrict__ plan,
-                                                           const int32_t* __restrict__ row_item, int n_splits_max,
+                                                           const int32_t* __restrict__ row_ctx, int n_splits_max,
                                                            int split_tokens)
 {
     const int64_t rh = blockIdx.x;                 // row * hq + head
     const int row = (int)(rh / a.hq);
     const int d = threadIdx.x;
-    const int32_t* e = plan + 4 + 4 * row_item[row];
-    const int P = a.prefix_lens ? a.prefix_lens[e[0]] : 0;
-    const int ctx = P + e[1] + e[2];               // as the split kernel cut the row's item
+    const int ctx = row_ctx[row];                  // as the split kernel cut the row's item
     const int part = part_tokens(ctx, split_tokens);
     const int n = (ctx + part - 1) / part;
-    const int64_t base = rh * n_splits_max;
-    float ms = -INFINITY;
-    for (int i = 0; i < n; ++i) ms = fmaxf(ms, ws_ml[(base + i) * 2]);     // finite: key 0 is visible to every row
-    float acc = 0.f, l = 0.f;
-    for (int i = 0; i < n; ++i) {                  // fixed order: reproducible
-        const float f = exp2f(ws_ml[(base + i) * 2] - ms);
-        acc += f * ws_o[(base + i) * D + d];
-        l += f * ws_ml[(base + i) * 2 + 1];
-    }
-    ((__bf16*)a.out)[rh * D + d] = (__bf16)(acc / l);
+    ((__bf16*)a.out)[rh * D + d] = (__bf16)merge_partials(ws_o, ws_ml, rh * n_splits_max, n, d);
 }
 
 inline int rows_per_group(int hq, int hkv) { return 16 / (hq / hkv); }
@@ -563,10 +554,10 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     float* ws_o = (float*)ws;
     float* ws_ml = ws_o + L.o_floats;
     int32_t* plan = (int32_t*)(ws_ml + L.ml_floats);
-    int32_t* row_item = plan + L.plan_ints;
+    int32_t* row_ctx = plan + L.plan_ints;
 
-    hipLaunchKernelGGL(merged_plan_kernel, dim3(1), dim3(256), 0, st, a.new_lens, a.cu_new, a.batch, a.total_rows, rk, rw,
-                       plan, row_item);
+    hipLaunchKernelGGL(merged_plan_kernel, dim3(1), dim3(256), 0, st, a.new_lens, a.prefix_lens, a.cu_new, a.batch,
+                       a.total_rows, rk, rw, plan, row_ctx);
     ag_status e = hip_check(hipGetLastError(), "merged plan launch");
     if (e) return e;
     const dim3 grid(nsm, a.c.hkv, (unsigned)items_max);
@@ -577,7 +568,7 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     prof_after(st);
     if ((e = hip_check(hipGetLastError(), "merged split launch"))) return e;
     hipLaunchKernelGGL(merged_merge_kernel, dim3((unsigned)((int64_t)a.total_rows * a.hq)), dim3(128), 0, st, a, ws_o, ws_ml,
-                       plan, row_item, nsm, split);
+                       row_ctx, nsm, split);
     return hip_check(hipGetLastError(), "merged merge launch");
 }
 

@@ -56,6 +56,38 @@ struct StepRegs {       // one wave's K and V operands for 32 tokens (two pages)
 };
 
 
+// The partials (m, l, O[D]) of one (row, head) lie at slots base .. base + n - 1 (n >= 1, the first of them with a
+// finite m); combine them in slot order - reproducible - four at a time, so that a group's loads are in flight
+// together instead of one dependent round trip per partial.  Returns channel d of the normalised output.
+__device__ __forceinline__ float merge_partials(const float* __restrict__ ws_o, const float* __restrict__ ws_ml,
+                                                int64_t base, int n, int d)
+{
+    float ms = -INFINITY, acc = 0.f, l = 0.f;
+    for (int i0 = 0; i0 < n; i0 += 4) {
+        float mi[4], li[4], oi[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int64_t p = base + min(i0 + j, n - 1);
+            mi[j] = ws_ml[p * 2];
+            li[j] = ws_ml[p * 2 + 1];
+            oi[j] = ws_o[p * D + d];
+            if (i0 + j >= n) mi[j] = -INFINITY;
+        }
+        const float m_new = fmaxf(fmaxf(ms, fmaxf(mi[0], mi[1])), fmaxf(mi[2], mi[3]));
+        const float keep = ms == -INFINITY ? 0.f : exp2f(ms - m_new);
+        acc *= keep;
+        l *= keep;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float f = mi[j] == -INFINITY ? 0.f : exp2f(mi[j] - m_new);     // a partial that saw no key
+            acc += f * oi[j];
+            l += f * li[j];
+        }
+        ms = m_new;
+    }
+    return acc / l;
+}
+
 // Workspace is sized for the smallest split a launcher may choose.
 constexpr int kMinSplit = 256;
 inline int splits_for(int max_ctx, int split) { return max_ctx <= 0 ? 1 : (max_ctx + split - 1) / split; }
