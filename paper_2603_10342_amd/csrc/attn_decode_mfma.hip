@@ -131,6 +131,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
 
     for (int f = f0; f < f1 && s < B;) {                 // one segment per pass; every value here is uniform
         const int k = min(n - u, f1 - f);                // steps of this segment, 1 .. q
+        if (k <= 0) break;                               // (only if the lengths changed under the kernel: never spin)
         const int per = (k + 3) >> 2;                    // steps per wave, at most kMaxSteps / 4 = 32
         const int my_u = u + w * per;
         const int my_n = max(0, min(per, k - w * per));
