@@ -37,6 +37,7 @@
 // contiguous range of KV heads, and inside it session-major, longest query
 // tile first: the workgroups resident together read one session's K/V for one
 // KV head, which then stays in that XCD's L2.
+#include <algorithm>
 #include <atomic>
 
 #include "ag_internal.h"
@@ -164,11 +165,17 @@ __device__ __forceinline__ void exp_tile(const f32x16 (&sc)[2], float sl2, float
 
 // NW waves per workgroup (4 or 8), 32 query rows each.  Eight waves halve the K/V bytes moved per flop (a tile
 // is shared by twice the rows) at the price of coarser query tiles.
-template <int NW>
-__global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int q_tiles,
+// GP: query heads per workgroup.  GP = 1: the NW waves are 32 * NW consecutive tokens of one head.  GP = G (the
+// heads of a KV-head group, which share K and V): wave w is head w % GP of tokens 32 * (w / GP) .. + 31, so the
+// workgroup covers 32 * NW / GP tokens of all G heads.  The rows per K/V tile are the same, but a chunk is cut
+// every 32 * NW / GP tokens instead of every 32 * NW (ragged chunks fill their last tile better) and all waves
+// of a workgroup end within one tile of each other on the diagonal.
+template <int NW, int GP>
+__global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int tiles_max,
                                                                                          int per_xcd, int64_t total_work)
 {
-    constexpr int BM = 32 * NW;             // query rows per workgroup
+    static_assert(NW % GP == 0, "the heads of a group share the workgroup's waves evenly");
+    constexpr int BM = 32 * NW / GP;        // tokens per workgroup
     constexpr int kPer = 16 / NW;           // direct-load instructions per wave for a K tile, and for a V tile
     constexpr int kVStages = v_stages(NW);
     constexpr int kVLead = kVStages - 2;    // V(t + kVLead) is requested in iteration t
@@ -179,17 +186,44 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
     const int64_t wk = (int64_t)xcd * per_xcd + ord;
     if (wk >= total_work) return;
     const int hkv = a.c.hkv, hq = a.hq, G = hq / hkv;
-    // work order: KV head, then session, then query tile (longest first), then the G heads of the group
-    const int per_sess = q_tiles * G;
-    const int g = (int)(wk / ((int64_t)a.batch * per_sess));
-    const int rem = (int)(wk % ((int64_t)a.batch * per_sess));
-    const int s = rem / per_sess;
-    const int qt = q_tiles - 1 - (rem % per_sess) / G;
-    const int h = g * G + rem % G;
-
-    const int N = a.new_lens[s];
+    // Work order: KV head, then session, then query tile (longest first), then (GP = 1) the G heads of the group.
+    // The grid holds `tiles_max` tiles per KV head, a host-side bound on sum_s ceil(N_s / BM); which (session,
+    // tile) the workgroup's tile index means follows from the lengths, which every wave scans for itself (lane l
+    // of a pass holds session 64 * pass + l).  A grid of batch x ceil(max_new / BM) tiles would be mostly empty
+    // workgroups when chunk lengths differ much, and launching a workgroup of this size takes the dispatcher of
+    // an XCD most of a microsecond, whether it has work or not.
+    const int hpw = GP == 1 ? G : 1;                // workgroups a tile of tokens takes
+    const int per_head = tiles_max * hpw;
+    const int g = (int)(wk / per_head);
+    const int rem = (int)(wk % per_head);
+    const int j = rem / hpw;                        // tile index among the KV head's tiles
+    int s = -1, qt = 0, N = 0;
+    {
+        const int ln = threadIdx.x & 63;
+        int before = 0;                             // tiles of the sessions of earlier passes
+        for (int s0 = 0; s0 < a.batch; s0 += 64) {
+            const int len = s0 + ln < a.batch ? a.new_lens[s0 + ln] : 0;
+            const int cnt = (len + BM - 1) / BM;
+            int incl = cnt;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int t = __shfl_up(incl, d);
+                if (ln >= d) incl += t;
+            }
+            const int pass_total = __builtin_amdgcn_readlane(incl, 63);
+            if (j < before + pass_total) {          // uniform
+                const unsigned long long hit = __builtin_amdgcn_ballot_w64(j < before + incl);
+                const int l = __builtin_ctzll(hit);                  // first session whose tiles reach past j
+                s = s0 + l;
+                N = __builtin_amdgcn_readlane(len, l);
+                qt = before + __builtin_amdgcn_readlane(incl, l) - 1 - j;   // the session's tiles, longest first
+                break;
+            }
+            before += pass_total;
+        }
+    }
+    if (s < 0) return;                              // beyond the batch's tiles
     const int q0 = qt * BM;
-    if (q0 >= N) return;
     const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
     const int ctx = P + N;
     const int64_t t_base = (int64_t)a.cu_new[s] + q0;
@@ -198,8 +232,9 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
     const int wu = __builtin_amdgcn_readfirstlane(w);           // the same value, known to be uniform: used only
                                                                  // where a scalar is required (page ids, M0)
     const int n = lane & 31, hi = lane >> 5;
-    const int rows_wg = min(BM, N - q0);            // valid query rows of this workgroup
-    const int qrow0 = 32 * w;                       // first row of this wave inside the tile
+    const int rows_wg = min(BM, N - q0);            // valid tokens of this workgroup
+    const int qrow0 = 32 * (w / GP);                // first token of this wave inside the tile
+    const int h = g * G + (GP == 1 ? rem % G : w % GP);     // this wave's query head
     const int rows_w = max(0, min(32, rows_wg - qrow0));
 
     const int n_tiles = (P + q0 + rows_wg - 1) / BN + 1;                        // tiles the workgroup stages
@@ -451,37 +486,46 @@ bool prefill_mfma_supported(const AttnArgs& a)
            (((uintptr_t)a.q | (uintptr_t)a.out | (uintptr_t)a.c.k | (uintptr_t)a.c.v) % 16 == 0);
 }
 
-template <int NW>
+template <int NW, int GP>
 static ag_status launch_prefill_nw(const AttnArgs& a, hipStream_t st)
 {
     static std::atomic<bool> attr_set{false};
     if (!attr_set.load()) {
-        ag_status e = hip_check(hipFuncSetAttribute((const void*)prefill_mfma_kernel<NW>,
+        ag_status e = hip_check(hipFuncSetAttribute((const void*)prefill_mfma_kernel<NW, GP>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes(NW)),
                                 "hipFuncSetAttribute(prefill)");
         if (e) return e;
         attr_set.store(true);
     }
-    constexpr int BM = 32 * NW;
-    const int q_tiles = (a.max_new + BM - 1) / BM;
-    const int64_t total = (int64_t)a.batch * a.hq * q_tiles;
+    constexpr int BM = 32 * NW / GP;
+    // sum_s ceil(N_s / BM) <= total_new / BM + batch, and no session has more than ceil(max_new / BM)
+    const int64_t tiles_max = std::min<int64_t>((int64_t)a.total_rows / BM + a.batch,
+                                                (int64_t)a.batch * ((a.max_new + BM - 1) / BM));
+    const int64_t total = (GP == 1 ? a.hq : a.c.hkv) * tiles_max;
     const int64_t per_xcd = (total + 7) / 8;
     if (per_xcd * 8 > 0x7fffffff) { set_error("too many query tiles for one launch"); return AG_ERR_INVALID_ARG; }
     prof_before(st);
-    hipLaunchKernelGGL(prefill_mfma_kernel<NW>, dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), lds_bytes(NW), st, a, q_tiles,
-                       (int)per_xcd, total);
+    hipLaunchKernelGGL((prefill_mfma_kernel<NW, GP>), dim3((unsigned)(per_xcd * 8)), dim3(64 * NW), lds_bytes(NW), st, a,
+                       (int)tiles_max, (int)per_xcd, total);
     prof_after(st);
     return hip_check(hipGetLastError(), "prefill launch");
 }
 
 ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
 {
-#ifdef AG_PREFILL_FORCE_NW
-    return launch_prefill_nw<AG_PREFILL_FORCE_NW>(a, st);
+    const int G = a.hq / a.c.hkv;
+#ifdef AG_PREFILL_NO_HEAD_PACKING
+    const bool pack = false;
 #else
+    const bool pack = G == 4;           // (the group sizes 2 and 8 would take their own instantiations)
+#endif
     // 256-row tiles when chunks are long enough to fill them (a K/V tile then feeds twice the rows);
     // 128-row tiles keep short, ragged chunks efficient
-    return a.max_new >= 512 ? launch_prefill_nw<8>(a, st) : launch_prefill_nw<4>(a, st);
+    if (pack) return a.max_new >= 512 ? launch_prefill_nw<8, 4>(a, st) : launch_prefill_nw<4, 4>(a, st);
+#ifdef AG_PREFILL_FORCE_NW
+    return launch_prefill_nw<AG_PREFILL_FORCE_NW, 1>(a, st);
+#else
+    return a.max_new >= 512 ? launch_prefill_nw<8, 1>(a, st) : launch_prefill_nw<4, 1>(a, st);
 #endif
 }
 
