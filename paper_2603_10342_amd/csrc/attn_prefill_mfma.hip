@@ -521,6 +521,9 @@ ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
 #endif
     // 256-row tiles when chunks are long enough to fill them (a K/V tile then feeds twice the rows);
     // 128-row tiles keep short, ragged chunks efficient
+#ifdef AG_PREFILL_FORCE_NW
+    if (pack) return launch_prefill_nw<AG_PREFILL_FORCE_NW, 4>(a, st);
+#endif
     if (pack) return a.max_new >= 512 ? launch_prefill_nw<8, 4>(a, st) : launch_prefill_nw<4, 4>(a, st);
 #ifdef AG_PREFILL_FORCE_NW
     return launch_prefill_nw<AG_PREFILL_FORCE_NW, 1>(a, st);
