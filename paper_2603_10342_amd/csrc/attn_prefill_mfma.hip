@@ -514,22 +514,20 @@ static ag_status launch_prefill_nw(const AttnArgs& a, hipStream_t st)
 ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
 {
     const int G = a.hq / a.c.hkv;
-#ifdef AG_PREFILL_NO_HEAD_PACKING
-    const bool pack = false;
-#else
-    const bool pack = G == 4;           // (the group sizes 2 and 8 would take their own instantiations)
-#endif
-    // 256-row tiles when chunks are long enough to fill them (a K/V tile then feeds twice the rows);
-    // 128-row tiles keep short, ragged chunks efficient
+    // 256-row workgroups when chunks are long enough to fill them (a K/V tile then feeds twice the rows);
+    // 128-row workgroups keep short, ragged chunks efficient.  Groups of 2, 4 or 8 query heads share a workgroup
+    // (a group of 8 only fits the 256-row form).
 #ifdef AG_PREFILL_FORCE_NW
-    if (pack) return launch_prefill_nw<AG_PREFILL_FORCE_NW, 4>(a, st);
-#endif
-    if (pack) return a.max_new >= 512 ? launch_prefill_nw<8, 4>(a, st) : launch_prefill_nw<4, 4>(a, st);
-#ifdef AG_PREFILL_FORCE_NW
-    return launch_prefill_nw<AG_PREFILL_FORCE_NW, 1>(a, st);
+    const bool big = AG_PREFILL_FORCE_NW == 8;
 #else
-    return a.max_new >= 512 ? launch_prefill_nw<8, 1>(a, st) : launch_prefill_nw<4, 1>(a, st);
+    const bool big = a.max_new >= 512;
 #endif
+#ifndef AG_PREFILL_NO_HEAD_PACKING
+    if (G == 4) return big ? launch_prefill_nw<8, 4>(a, st) : launch_prefill_nw<4, 4>(a, st);
+    if (G == 2) return big ? launch_prefill_nw<8, 2>(a, st) : launch_prefill_nw<4, 2>(a, st);
+    if (G == 8) return launch_prefill_nw<8, 8>(a, st);
+#endif
+    return big ? launch_prefill_nw<8, 1>(a, st) : launch_prefill_nw<4, 1>(a, st);
 }
 
 }  // namespace ag

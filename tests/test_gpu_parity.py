@@ -247,6 +247,22 @@ def test_cold_prefill_head_groupings(hq, hkv):
     check_close(got, ref, g.dtype, "cold gqa")
 
 
+@pytest.mark.parametrize("hq,hkv", [(4, 2), (8, 2), (16, 2), (3, 1)])
+def test_long_chunks_with_head_groups_sharing_a_workgroup(hq, hkv):
+    """Chunks of 512 rows and more take the 256-row workgroups; groups of 2, 4 and 8 heads share one (a wave is
+    one head x 32 tokens), a group of 3 does not.  Cold, then a resume on top, ragged ends included."""
+    g = slm(pages=256, hq=hq, hkv=hkv)
+    bt = I.deal_block_tables(I.rng_for(14, 0), [1130, 78, 546], 16, g.num_pages)
+    cold = make_batch(g, [0, 0, 0], [600, 77, 513], seed=14, bt=bt, sigma_qk=1.0, sigma_v=1.0)
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    got, ref = run_phase(cache, kp, vp, cold, "cold")
+    check_close(got, ref, g.dtype, "cold, shared workgroups")
+    more = make_batch(g, [600, 77, 513], [530, 1, 33], seed=14, bt=bt, stream=2, sigma_qk=1.0, sigma_v=1.0)
+    got, ref = run_phase(cache, kp, vp, more, "resume")
+    check_close(got, ref, g.dtype, "resume, shared workgroups")
+
+
 @pytest.mark.parametrize("p,n", [([5, 16, 100], [40, 1, 130]), ([64, 63, 65], [64, 65, 63]), ([700, 0], [150, 20])])
 def test_resume_prefill_offsets(p, n):
     g = slm(pages=256)
