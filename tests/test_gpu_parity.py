@@ -263,6 +263,27 @@ def test_long_chunks_with_head_groups_sharing_a_workgroup(hq, hkv):
     check_close(got, ref, g.dtype, "resume, shared workgroups")
 
 
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (3, 1)])
+def test_resume_over_many_short_sessions(hq, hkv):
+    """150 sessions with chunks of 0..40 rows on prefixes of 0..100 tokens: the workgroups' tile list is
+    resolved from the lengths in passes of 64 sessions, and many sessions bring no tile at all."""
+    g = slm(pages=1400, hq=hq, hkv=hkv)
+    rng = np.random.default_rng(44)
+    p = rng.integers(0, 101, size=150)
+    n = rng.integers(0, 41, size=150)
+    n[rng.integers(0, 150, size=30)] = 0
+    n[[0, 63, 64, 127, 128, 149]] = [0, 40, 0, 1, 33, 0]        # around the passes' boundaries
+    bt = I.deal_block_tables(I.rng_for(44, 0), np.maximum(p + n, 1), 16, g.num_pages)
+    fill = make_batch(g, np.zeros_like(p), p, seed=44, bt=bt, sigma_qk=1.0, sigma_v=1.0)
+    cache = make_cache(g)
+    kp, vp = fresh_pools(g)
+    gpu_append(cache, DevBatch(fill))
+    oracle_append(kp, vp, fill)
+    chunk = make_batch(g, p, n, seed=44, bt=bt, stream=2, sigma_qk=1.0, sigma_v=1.0)
+    got, ref = run_phase(cache, kp, vp, chunk, "resume")
+    check_close(got, ref, g.dtype, "resume, 150 sessions")
+
+
 @pytest.mark.parametrize("p,n", [([5, 16, 100], [40, 1, 130]), ([64, 63, 65], [64, 65, 63]), ([700, 0], [150, 20])])
 def test_resume_prefill_offsets(p, n):
     g = slm(pages=256)
