@@ -201,25 +201,31 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
     {
         const int ln = threadIdx.x & 63;
         int before = 0;                             // tiles of the sessions of earlier passes
-        for (int s0 = 0; s0 < a.batch; s0 += 64) {
-            const int len = s0 + ln < a.batch ? a.new_lens[s0 + ln] : 0;
-            const int cnt = (len + BM - 1) / BM;
-            int incl = cnt;
+        for (int s0 = 0; s0 < a.batch && s < 0; s0 += 256) {
+            int lens[4];                            // four passes' lengths are fetched together
 #pragma unroll
-            for (int d = 1; d < 64; d <<= 1) {
-                const int t = __shfl_up(incl, d);
-                if (ln >= d) incl += t;
+            for (int k = 0; k < 4; ++k) lens[k] = s0 + 64 * k + ln < a.batch ? a.new_lens[s0 + 64 * k + ln] : 0;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (s >= 0) break;                  // uniform
+                const int len = lens[k];
+                const int cnt = (len + BM - 1) / BM;
+                int incl = cnt;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int t = __shfl_up(incl, d);
+                    if (ln >= d) incl += t;
+                }
+                const int pass_total = __builtin_amdgcn_readlane(incl, 63);
+                if (j < before + pass_total) {      // uniform
+                    const unsigned long long hit = __builtin_amdgcn_ballot_w64(j < before + incl);
+                    const int l = __builtin_ctzll(hit);              // first session whose tiles reach past j
+                    s = s0 + 64 * k + l;
+                    N = __builtin_amdgcn_readlane(len, l);
+                    qt = before + __builtin_amdgcn_readlane(incl, l) - 1 - j;   // the session's tiles, longest first
+                }
+                before += pass_total;
             }
-            const int pass_total = __builtin_amdgcn_readlane(incl, 63);
-            if (j < before + pass_total) {          // uniform
-                const unsigned long long hit = __builtin_amdgcn_ballot_w64(j < before + incl);
-                const int l = __builtin_ctzll(hit);                  // first session whose tiles reach past j
-                s = s0 + l;
-                N = __builtin_amdgcn_readlane(len, l);
-                qt = before + __builtin_amdgcn_readlane(incl, l) - 1 - j;   // the session's tiles, longest first
-                break;
-            }
-            before += pass_total;
         }
     }
     if (s < 0) return;                              // beyond the batch's tiles
