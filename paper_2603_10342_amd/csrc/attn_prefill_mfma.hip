@@ -5,9 +5,12 @@
 //
 // A dense contraction, bound by the matrix cores: 4 * D flop per visible
 // (query, key) pair and head.  One workgroup of NW waves (4 or 8) owns 32 * NW
-// consecutive query rows of one (session, query head); each wave owns 32 rows
-// and keeps their Q in registers.  Keys and values are taken 64 at a time
-// (4 pages) and staged through LDS by direct global-to-LDS loads:
+// query rows of one session: consecutive tokens of one query head, or - when
+// the KV-head group has 2, 4 or 8 query heads - fewer tokens of all the
+// group's heads, which share K and V (see the kernel's GP parameter); each
+// wave owns 32 tokens of one head and keeps their Q in registers.  Keys and
+// values are taken 64 at a time (4 pages) and staged through LDS by direct
+// global-to-LDS loads:
 //
 //   S^T[key][query] = K[key][:] . Q[query][:]      2 x 8 MFMA 32x32x16
 //   softmax weights per query column (reference m, running sum l, exp2)
@@ -36,7 +39,10 @@
 // Workgroups are numbered so that the XCD a workgroup lands on (id % 8) owns a
 // contiguous range of KV heads, and inside it session-major, longest query
 // tile first: the workgroups resident together read one session's K/V for one
-// KV head, which then stays in that XCD's L2.
+// KV head, which then stays in that XCD's L2.  The grid lists the batch's real
+// tiles only (each workgroup finds its tile from the chunk lengths): empty
+// workgroups are not free, the dispatcher takes as long over them as over
+// the others.
 #include <algorithm>
 #include <atomic>
 
