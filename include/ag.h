@@ -164,8 +164,9 @@ AG_API ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* o
  * ag_attn_resume's: session s brings new_lens[s] >= 0 query rows at positions prefix_lens[s] + i that attend
  * causally to the session's keys; a decode is the case new_lens[s] = 1, prefix_lens[s] = ctx - 1.  What
  * differs is the schedule: the keys of each session are split over workgroups as in ag_attn_decode, which
- * pays when sessions bring few rows (the launch is then bound by reading K and V); for chunks of hundreds of
- * rows ag_attn_resume is the faster call.  Arguments as ag_attn_resume, plus a device workspace of at least
+ * pays when sessions bring few rows (the launch is then bound by reading K and V); when the longest chunk
+ * (max_new) has about a hundred rows or more the call runs ag_attn_resume's kernel instead, which is faster
+ * from there on.  Arguments as ag_attn_resume, plus a device workspace of at least
  * ag_attn_merged_workspace_bytes(total_new, num_q_heads, max_ctx) bytes, 16-byte aligned, which the call may
  * overwrite entirely (AG_ERR_WORKSPACE if smaller).  Calls sharing a workspace must be ordered on one stream.
  */
