@@ -159,6 +159,25 @@ AG_API ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* o
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * ag_attn_decode for callers that cannot allocate device memory or pass a workspace: code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * bit-identical results, but the partials go through an array of AG_DECODE_STATIC_SCRATCH_BYTES bytes that is
+ * part of the library's device image (one copy on every GPU the library runs on, held until the process
+ * ends).  The call allocates and frees nothing; its first use on a device looks the array's address up once.
+ * A step whose ag_attn_decode_workspace_bytes() exceeds AG_DECODE_STATIC_SCRATCH_BYTES is refused with
+ * AG_ERR_WORKSPACE before anything is enqueued (config-2-sized steps - 64 sessions, 32 query heads, contexts
+ * to 4096 - need 18.1 MB).  Nothing in the array has to start at zero and nothing is kept between calls, but
+ * every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different streams, no event
+ * between them) race; order them on one stream or with events.
+ */
+#define AG_DECODE_STATIC_SCRATCH_BYTES (32u << 20)
+AG_API ag_status ag_attn_decode_static(const ag_kv_cache* cache, const void* q, void* out,    /* device [B][Hq][D] */
+                                const int32_t* block_tables, int32_t max_pages_per_seq,
+                                const int32_t* ctx_lens,                               /* device [B] */
+                                int32_t batch, int32_t max_ctx,
+                                int32_t num_q_heads, float scale, void* stream);
+
+/*
  * The decode queue's batch in one launch (paper Sec. III-A: short resume prefills are merged with decodes;
  * Algorithm 1: a request joins Q_D if it is a decode or no longer than B_prefill).  Semantics are exactly
  * ag_attn_resume's: session s brings new_lens[s] >= 0 query rows at positions prefix_lens[s] + i that attend

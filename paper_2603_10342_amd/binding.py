@@ -22,6 +22,7 @@ AG_F32, AG_BF16 = 0, 1
 
 EXPORTS = [
     "ag_kv_append", "ag_attn_prefill", "ag_attn_resume", "ag_attn_decode_workspace_bytes", "ag_attn_decode",
+    "ag_attn_decode_static",
     "ag_attn_merged_workspace_bytes", "ag_attn_merged",
     "ag_stream_create_cumask", "ag_stream_destroy", "ag_cumask_build", "ag_probe_placement", "ag_device_info",
     "ag_debug_validate", "ag_prof_enable", "ag_prof_collect", "ag_prof_disable", "ag_status_string",
@@ -90,6 +91,7 @@ def lib():
     l.ag_attn_decode_workspace_bytes.argtypes = [i32, i32, i32, i32]
     l.ag_attn_decode_workspace_bytes.restype = C.c_size_t
     l.ag_attn_decode.argtypes = [cp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp, C.c_size_t, vp]
+    l.ag_attn_decode_static.argtypes = [cp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp]
     l.ag_attn_merged_workspace_bytes.argtypes = [i32, i32, i32]
     l.ag_attn_merged_workspace_bytes.restype = C.c_size_t
     l.ag_attn_merged.argtypes = [cp, vp, vp, i32p, i32, i32p, i32p, i32p, i32, i32, i32, i32, i32, C.c_float, vp,
@@ -243,6 +245,17 @@ def ag_attn_decode(cache: KVCache, q, out, block_tables, ctx_lens, max_ctx: int,
     _check(lib().ag_attn_decode(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
                                 _i32(ctx_lens), ctx_lens.shape[0], max_ctx, num_q_heads, scale, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+AG_DECODE_STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def ag_attn_decode_static(cache: KVCache, q, out, block_tables, ctx_lens, max_ctx: int, num_q_heads: int, scale: float,
+                          stream=None):
+    c = cache.c_struct()
+    _check(lib().ag_attn_decode_static(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
+                                       _i32(ctx_lens), ctx_lens.shape[0], max_ctx, num_q_heads, scale,
+                                       _stream(stream)))
 
 
 def ag_attn_merged_workspace_bytes(total_new: int, num_q_heads: int, max_ctx: int) -> int:

@@ -217,9 +217,12 @@ size_t ag_attn_decode_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_
     return decode_workspace_bytes(batch, num_q_heads, head_dim, max_ctx);
 }
 
-ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* out, const int32_t* block_tables,
-                         int32_t max_pages_per_seq, const int32_t* ctx_lens, int32_t batch, int32_t max_ctx,
-                         int32_t num_q_heads, float scale, void* workspace, size_t workspace_bytes, void* stream)
+// Shared body of the two decode entry points.  own_scratch: the workspace is the library's static array
+// (looked up only after every host-side check has passed) instead of the caller's.
+static ag_status decode_common(const ag_kv_cache* cache, const void* q, void* out, const int32_t* block_tables,
+                               int32_t max_pages_per_seq, const int32_t* ctx_lens, int32_t batch, int32_t max_ctx,
+                               int32_t num_q_heads, float scale, void* workspace, size_t workspace_bytes,
+                               bool own_scratch, void* stream)
 {
     CacheView c;
     ag_status st = view_cache(cache, &c);
@@ -235,11 +238,21 @@ ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* out, con
         return AG_ERR_INVALID_ARG;
     }
     const size_t need = decode_workspace_bytes(batch, num_q_heads, c.d, max_ctx);
-    if (workspace_bytes < need || (need && !workspace)) {
-        set_error("decode workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
-        return AG_ERR_WORKSPACE;
+    if (own_scratch) {
+        if (need > (size_t)AG_DECODE_STATIC_SCRATCH_BYTES) {
+            set_error("decode step needs %zu bytes of workspace, the library's own scratch holds %zu: reduce batch * "
+                      "num_q_heads * max_ctx or call ag_attn_decode with a workspace", need,
+                      (size_t)AG_DECODE_STATIC_SCRATCH_BYTES);
+            return AG_ERR_WORKSPACE;
+        }
+        if ((st = decode_static_scratch(&workspace))) return st;
+    } else {
+        if (workspace_bytes < need || (need && !workspace)) {
+            set_error("decode workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+            return AG_ERR_WORKSPACE;
+        }
+        if (((uintptr_t)workspace) % 16) { set_error("decode workspace must be 16-byte aligned"); return AG_ERR_INVALID_ARG; }
     }
-    if (((uintptr_t)workspace) % 16) { set_error("decode workspace must be 16-byte aligned"); return AG_ERR_INVALID_ARG; }
 
     AttnArgs a;
     a.q = q; a.out = out; a.c = c; a.bt = block_tables; a.max_pages = max_pages_per_seq;
@@ -247,6 +260,22 @@ ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* out, con
     a.batch = batch; a.total_rows = batch; a.max_new = 1; a.max_ctx = max_ctx; a.hq = num_q_heads; a.scale = scale;
     if (decode_mfma_supported(a)) return launch_decode_mfma(a, workspace, (hipStream_t)stream);
     return launch_attn_general(a, (hipStream_t)stream);
+}
+
+ag_status ag_attn_decode(const ag_kv_cache* cache, const void* q, void* out, const int32_t* block_tables,
+                         int32_t max_pages_per_seq, const int32_t* ctx_lens, int32_t batch, int32_t max_ctx,
+                         int32_t num_q_heads, float scale, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return decode_common(cache, q, out, block_tables, max_pages_per_seq, ctx_lens, batch, max_ctx, num_q_heads, scale,
+                         workspace, workspace_bytes, false, stream);
+}
+
+ag_status ag_attn_decode_static(const ag_kv_cache* cache, const void* q, void* out, const int32_t* block_tables,
+                                int32_t max_pages_per_seq, const int32_t* ctx_lens, int32_t batch, int32_t max_ctx,
+                                int32_t num_q_heads, float scale, void* stream)
+{
+    return decode_common(cache, q, out, block_tables, max_pages_per_seq, ctx_lens, batch, max_ctx, num_q_heads, scale,
+                         nullptr, 0, true, stream);
 }
 
 ag_status ag_stream_create_cumask(void** stream_out, const uint32_t* cu_mask_words, int32_t n_words)

@@ -37,8 +37,14 @@
 //   partials of the pair's segments in order (reproducible) and writes bf16.
 #include <algorithm>
 #include <atomic>
+#include <mutex>
 
 #include "attn_split_common.h"
+
+// Workspace of ag_attn_decode_static: the decode step's header and partials for callers that cannot hand over
+// device memory of their own.  One copy per GPU the library runs on, held until the process ends.  In host code
+// the name below is only a handle for hipGetSymbolAddress; kernels and copies get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[AG_DECODE_STATIC_SCRATCH_BYTES];
 
 namespace ag {
 
@@ -358,6 +364,26 @@ bool decode_mfma_supported(const AttnArgs& a)
 {
     return a.c.dtype == AG_BF16 && a.c.d == D && a.c.ps == PS && (a.hq / a.c.hkv) <= 16 &&
            (((uintptr_t)a.q | (uintptr_t)a.c.k | (uintptr_t)a.c.v) % 16 == 0);
+}
+
+ag_status decode_static_scratch(void** ptr_out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* ptrs[kMaxDevices] = {};
+    int dev = -1;
+    ag_status e = hip_check(hipGetDevice(&dev), "hipGetDevice");
+    if (e) return e;
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device %d is beyond the %d devices the static scratch is kept for", dev, kMaxDevices); return AG_ERR_UNSUPPORTED; }
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptrs[dev]) {                   // each device holds its own copy of the array at its own address
+        void* p = nullptr;
+        if ((e = hip_check(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)"))) return e;
+        if (!p) { set_error("hipGetSymbolAddress(scratch) returned a null address"); return AG_ERR_HIP; }
+        ptrs[dev] = p;
+    }
+    *ptr_out = ptrs[dev];
+    return AG_OK;
 }
 
 ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st)

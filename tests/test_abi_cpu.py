@@ -53,6 +53,11 @@ def test_null_and_shape_errors_come_from_the_host_layer():
     assert l.ag_attn_resume(C.byref(ok), 16, 16, 16, 4, 16, 16, 16, 1, 16, 16, 65, 4, 0.1, None) == B.AG_ERR_INVALID_ARG
     assert l.ag_attn_decode(C.byref(ok), 16, 16, 16, 4, 16, 1, 64, 4, 0.1, 16, 8, None) == B.AG_ERR_WORKSPACE
     assert l.ag_attn_decode(C.byref(ok), 16, 16, 16, 4, 16, 1, 65, 4, 0.1, 16, 1 << 20, None) == B.AG_ERR_INVALID_ARG
+    # the static-scratch decode refuses, on the host, a step larger than its array (and checks its arguments first)
+    assert l.ag_attn_decode_static(C.byref(ok), 16, 16, 16, 8192, 16, 512, 131072, 32, 0.1, None) == B.AG_ERR_WORKSPACE
+    assert b"scratch" in l.ag_last_error()
+    assert l.ag_attn_decode_static(C.byref(ok), 16, 16, 16, 4, 16, 1, 65, 4, 0.1, None) == B.AG_ERR_INVALID_ARG
+    assert l.ag_attn_decode_static(C.byref(ok), None, 16, 16, 4, 16, 1, 64, 4, 0.1, None) == B.AG_ERR_INVALID_ARG
     # zero new tokens is a no-op that never reaches the device
     assert l.ag_kv_append(C.byref(ok), 16, 16, 16, 4, 16, 16, 16, 1, 0, None) == B.AG_OK
     assert l.ag_attn_prefill(C.byref(ok), 16, 16, 16, 4, 16, 16, 1, 0, 0, 4, 0.1, None) == B.AG_OK
