@@ -1,6 +1,8 @@
 """Parity at the benchmark configurations' full sizes, through the same entry points and launch shapes
-bench.py times.  The oracle checks every decode row (cheap) and a seeded sample of prefill rows chosen
-to cover tile edges, session ends and random interior rows; KV pools are compared bit for bit."""
+bench.py times.  The oracle checks every decode row (cheap) and, for the prefills, the first, the last and a
+seeded interior row of EVERY block of 32 consecutive query rows of every session - the rows one wave of the
+matrix-core kernel owns, so every wave of every workgroup of the launched grid is compared on all its heads -
+plus the edges around tile boundaries; KV pools are compared bit for bit."""
 import numpy as np
 import pytest
 import torch
@@ -22,18 +24,19 @@ def pools_equal_on_device(cache, kp, vp, dtype):
         del ref
 
 
-def sample_rows(b, rng, n_random, edges=(0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256)):
+def sample_rows(b, rng, block=32, edges=(0, 1, 31, 32, 63, 64, 127, 128, 129, 255, 256)):
+    """(session, row) pairs: for every session, the first, the last and one seeded interior row of each block of
+    `block` consecutive rows, and the rows around the first tile boundaries and the session's end."""
     rs, ri = [], []
     for s in range(b.batch):
         n = int(b.new_lens[s])
-        picks = {e for e in edges if e < n} | {n - 1, n - 2, n - 128, n // 2} if n > 1 else {0}
+        picks = {e for e in edges if e < n} | {n - 1, n - 2, n - 128, n // 2}
+        for r0 in range(0, n, block):
+            r1 = min(r0 + block, n) - 1
+            picks |= {r0, r1, int(rng.integers(r0, r1 + 1))}
         for i in sorted(p for p in picks if 0 <= p < n):
             rs.append(s)
             ri.append(i)
-    extra_s = rng.integers(0, b.batch, size=n_random)
-    for s in extra_s:
-        rs.append(int(s))
-        ri.append(int(rng.integers(0, b.new_lens[s])))
     return np.array(rs, np.int32), np.array(ri, np.int32)
 
 
@@ -58,7 +61,7 @@ def test_config2_decode_full():
     check_close(got, ref, g.dtype, "config 2 decode")
 
 
-def test_config3_cold_prefill_sampled():
+def test_config3_cold_prefill_every_wave_block():
     b = I.make_cold()
     g = b.geom
     cache = make_cache(g)
@@ -70,12 +73,12 @@ def test_config3_cold_prefill_sampled():
     pools_equal_on_device(cache, kp, vp, g.dtype)
     got = gpu_prefill(cache, d)
     assert np.isfinite(got).all()
-    rows = sample_rows(b, I.rng_for(I.config_seed(3), 9), 96)
+    rows = sample_rows(b, I.rng_for(I.config_seed(3), 9))
     ref = oracle_attn(kp, vp, b, rows=rows)
     check_rows(got, b, rows, ref, "config 3 cold prefill")
 
 
-def test_config4_resume_prefill_sampled():
+def test_config4_resume_prefill_every_wave_block():
     c = I.make_resume()
     g = c.geom
     cache = make_cache(g)
@@ -88,12 +91,12 @@ def test_config4_resume_prefill_sampled():
     d = DevBatch(c.chunk)
     got = gpu_resume(cache, d)
     assert np.isfinite(got).all()
-    rows = sample_rows(c.chunk, I.rng_for(I.config_seed(4), 9), 64)
+    rows = sample_rows(c.chunk, I.rng_for(I.config_seed(4), 9))
     ref = oracle_attn(kp, vp, c.chunk, rows=rows)
     check_rows(got, c.chunk, rows, ref, "config 4 resume prefill")
 
 
-def test_config5_shapes_sampled():
+def test_config5_shapes_one_call_after_another():
     m = I.make_mixed()
     g = m.geom
     cache = make_cache(g)
@@ -105,10 +108,10 @@ def test_config5_shapes_sampled():
     pools_equal_on_device(cache, kp, vp, g.dtype)
     dc, dr, dd = DevBatch(m.cold), DevBatch(m.resume), DevBatch(m.decode)
     got = gpu_prefill(cache, dc)
-    rows = sample_rows(m.cold, I.rng_for(I.config_seed(5), 9), 16)
+    rows = sample_rows(m.cold, I.rng_for(I.config_seed(5), 9))
     check_rows(got, m.cold, rows, oracle_attn(kp, vp, m.cold, rows=rows), "config 5 cold")
     got = gpu_resume(cache, dr)
-    rows = sample_rows(m.resume, I.rng_for(I.config_seed(5), 10), 32)
+    rows = sample_rows(m.resume, I.rng_for(I.config_seed(5), 10))
     check_rows(got, m.resume, rows, oracle_attn(kp, vp, m.resume, rows=rows), "config 5 resume")
     got = gpu_decode(cache, dd.q, dd.bt, dd.ctx, dd.max_ctx, g)
     ref = O.decode(kp, vp, g.dtype, m.decode.q, m.decode.block_tables, m.decode.ctx_lens, g.num_q_heads, g.scale)

@@ -8,7 +8,7 @@ import pytest
 import torch
 
 from gpu_helpers import DevBatch, check_close, make_cache, to_f64
-from helpers import fresh_pools, oracle_append
+from helpers import fresh_pools, make_batch, oracle_append, oracle_attn
 from oracle import controller as OC
 from oracle import oracle as O
 from paper_2603_10342_amd import binding as B
@@ -99,6 +99,8 @@ def test_bind_follows_the_partition_rule_and_later_launches_obey_it():
 
 
 def test_decode_and_resume_are_right_on_every_bound_entry():
+    """Both request classes on both streams of the bound entry: a decode step, and a resume prefill whose chunks
+    (130 and 70 rows on 700- and 300-token prefixes) run the matrix-core tile kernel."""
     g = I.Geometry(8, 2, 128, 16, 1024, I.BF16)
     c = I.make_decode(batch=6, lo=300, hi=1500, num_pages=1024, geom=g, seed=91, sigma_qk=1.0, sigma_v=1.0)
     cache = make_cache(g)
@@ -110,6 +112,17 @@ def test_decode_and_resume_are_right_on_every_bound_entry():
     ws = torch.empty(B.ag_attn_decode_workspace_bytes(6, 8, 128, step.max_ctx) // 4, dtype=torch.float32, device="cuda")
     B.ag_kv_append(cache, fill.k_new, fill.v_new, fill.bt, fill.prefix, fill.new, fill.cu, fill.total)
     B.ag_kv_append(cache, step.k_new, step.v_new, step.bt, step.prefix, step.new, step.cu, step.total)
+    # a resume batch on a cache of its own
+    bt_r = I.deal_block_tables(I.rng_for(92, 0), [830, 370], 16, g.num_pages)
+    r_fill = make_batch(g, [0, 0], [700, 300], seed=92, bt=bt_r)
+    r_chunk = make_batch(g, [700, 300], [130, 70], seed=92, bt=bt_r, stream=2)
+    cache_r = make_cache(g)
+    kpr, vpr = fresh_pools(g)
+    rf, rc = DevBatch(r_fill), DevBatch(r_chunk)
+    for b, d in ((r_fill, rf), (r_chunk, rc)):
+        B.ag_kv_append(cache_r, d.k_new, d.v_new, d.bt, d.prefix, d.new, d.cu, d.total)
+        oracle_append(kpr, vpr, b)
+    ref_r = oracle_attn(kpr, vpr, r_chunk)
     torch.cuda.synchronize()
     slots = B.Slots(8)
     try:
@@ -121,8 +134,12 @@ def test_decode_and_resume_are_right_on_every_bound_entry():
                     continue
                 out = torch.full_like(step.q, float("nan"))
                 B.ag_attn_decode(cache, step.q, out, step.bt, step.ctx, step.max_ctx, g.num_q_heads, g.scale, ws, stream=s)
+                out_r = torch.full_like(rc.q, float("nan"))
+                B.ag_attn_resume(cache_r, rc.q, out_r, rc.bt, rc.prefix, rc.new, rc.cu, rc.total, rc.max_new, rc.max_ctx,
+                                 g.num_q_heads, g.scale, stream=s)
                 torch.cuda.synchronize()
                 check_close(to_f64(out, g.dtype), ref, g.dtype, f"decode on {name} of entry for R={r}")
+                check_close(to_f64(out_r, g.dtype), ref_r, g.dtype, f"resume on {name} of entry for R={r}")
     finally:
         torch.cuda.synchronize()
         slots.close()
