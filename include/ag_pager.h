@@ -5,8 +5,8 @@
  * threads' kernels with events so that a decode never reads keys or values that are still being written.
  *
  * The manager is host-side bookkeeping over page NUMBERS of a pool the caller owns (ag_kv_cache in ag.h);
- * it allocates no device memory.  The only device objects it creates are one event per session (default
- * flags, timing disabled).  Every function is safe to call from several threads at once.
+ * it allocates no device memory.  The only device objects it creates are events (timing disabled): one per
+ * session for its writer and one per (session, reader stream) for its readers.  Every function is safe to call from several threads at once.
  *
  * Life of a session
  *   ag_pager_open      -> a session id with no pages
@@ -19,7 +19,14 @@
  *   ag_pager_acquire   -> a reader about to launch on another stream: makes that stream wait for the
  *                         session's last commit (no wait when it was committed on the same stream, or when
  *                         the event has already completed) and returns the sealed length
- *   ag_pager_close     -> waits for the session's event, then returns its pages to the free list
+ *   (reader)           -> enqueues its attention kernels on that stream
+ *   ag_pager_release   -> records, on the reader's stream and after those launches, that the session's pages
+ *                         are in use until this point of the stream
+ *   ag_pager_close     -> waits for the session's last commit AND for every release recorded for it, then
+ *                         returns its pages to the free list: a page is never handed to another session
+ *                         while a committed write or a released read of it may still be running.  A reader
+ *                         that never calls ag_pager_release is invisible to close (the caller must then order
+ *                         close after that reader itself).
  *
  * Errors: ag_status of ag.h; AG_ERR_NO_SPACE means not enough free pages (or sessions, or row capacity) and
  * that nothing was changed.  Messages through ag_last_error().
@@ -42,6 +49,8 @@ typedef struct ag_pager_stats {
     int64_t reserves, failed_reserves, commits;
     int64_t waits_issued;      /* ag_pager_acquire calls that made a stream wait for an event */
     int64_t waits_skipped;     /* ... that needed none: same stream, nothing pending, or already complete */
+    int64_t releases;          /* ag_pager_release calls */
+    int64_t close_waits;       /* events (writer's or readers') that ag_pager_close calls waited for */
 } ag_pager_stats;
 
 AG_API ag_status ag_pager_create(int32_t num_pages, int32_t page_size, int32_t max_sessions,
@@ -72,6 +81,14 @@ AG_API ag_status ag_pager_commit(ag_pager* pager, int32_t session, void* stream)
 
 /* See the header comment.  *sealed_len_out (may be NULL) receives the session's read-only length. */
 AG_API ag_status ag_pager_acquire(ag_pager* pager, int32_t session, void* stream, int32_t* sealed_len_out);
+
+/*
+ * A reader is done enqueueing: records an event on `stream` (the stream ag_pager_acquire was given) after the
+ * launches the caller has made there.  ag_pager_close waits for it before the session's pages can be reused
+ * (paper Sec. III-C: a decode never consumes partially written KV - which a page handed to another session's
+ * prefill while the decode still reads it would be).  One event per (session, stream), re-recorded by every call.
+ */
+AG_API ag_status ag_pager_release(ag_pager* pager, int32_t session, void* stream);
 
 /* Lengths of a session (any pointer may be NULL): tokens reserved, tokens sealed, pages held. */
 AG_API ag_status ag_pager_lengths(ag_pager* pager, int32_t session, int32_t* reserved_out, int32_t* sealed_out,

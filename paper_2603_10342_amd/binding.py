@@ -33,7 +33,7 @@ EXPORTS = [
     "ag_slots_get", "ag_slots_bind", "ag_slots_current",
     # ag_pager.h
     "ag_pager_create", "ag_pager_destroy", "ag_pager_open", "ag_pager_close", "ag_pager_reserve", "ag_pager_seal",
-    "ag_pager_commit", "ag_pager_acquire", "ag_pager_lengths", "ag_pager_export", "ag_pager_page_state",
+    "ag_pager_commit", "ag_pager_acquire", "ag_pager_release", "ag_pager_lengths", "ag_pager_export", "ag_pager_page_state",
     "ag_pager_get_stats",
 ]
 AG_PAGE_FREE, AG_PAGE_WRITABLE, AG_PAGE_SEALED = 0, 1, 2
@@ -62,7 +62,8 @@ class ag_ctl_state(C.Structure):
 class ag_pager_stats(C.Structure):
     _fields_ = [("num_pages", C.c_int32), ("free_pages", C.c_int32), ("open_sessions", C.c_int32),
                 ("reserves", C.c_int64), ("failed_reserves", C.c_int64), ("commits", C.c_int64),
-                ("waits_issued", C.c_int64), ("waits_skipped", C.c_int64)]
+                ("waits_issued", C.c_int64), ("waits_skipped", C.c_int64),
+                ("releases", C.c_int64), ("close_waits", C.c_int64)]
 
 
 class ag_kv_cache(C.Structure):
@@ -128,6 +129,7 @@ def lib():
     l.ag_pager_seal.argtypes = [vp, i32]
     l.ag_pager_commit.argtypes = [vp, i32, vp]
     l.ag_pager_acquire.argtypes = [vp, i32, vp, pi32]
+    l.ag_pager_release.argtypes = [vp, i32, vp]
     l.ag_pager_lengths.argtypes = [vp, i32, pi32, pi32, pi32]
     l.ag_pager_export.argtypes = [vp, pi32, i32, pi32]
     l.ag_pager_page_state.argtypes = [vp, i32]
@@ -464,6 +466,9 @@ class Pager:
         n = C.c_int32()
         _check(lib().ag_pager_acquire(self._h, session, _stream(stream), C.byref(n)))
         return n.value
+
+    def release(self, session: int, stream=None):
+        _check(lib().ag_pager_release(self._h, session, _stream(stream)))
 
     def lengths(self, session: int) -> dict:
         r, s, p = C.c_int32(), C.c_int32(), C.c_int32()

@@ -1,5 +1,7 @@
 // KV page manager (paper Sec. III-C, memory management): free list under a mutex, read-only marking of what
-// a committed prefill wrote, one event per session to order the writer's stream against readers' streams.
+// a committed prefill wrote, one event per session to order the writer's stream against readers' streams,
+// and one event per (session, reader stream) so that a closing session's pages are not handed out again
+// while a reader's kernels may still be reading them.
 // Host code; the only device objects are the events.
 #include <mutex>
 #include <new>
@@ -20,6 +22,13 @@ struct Session {
     hipEvent_t ev = nullptr;          // created at the first commit
     hipStream_t ev_stream = nullptr;  // where the last commit was recorded
     bool pending = false;             // the last commit's event may not have completed yet
+    struct Reader {                   // one per stream that has released the session (events are kept and reused)
+        hipStream_t stream = nullptr;
+        hipEvent_t ev = nullptr;
+        bool pending = false;         // recorded after the reader's launches and not known to have completed
+    };
+    std::vector<Reader> readers;
+    uint64_t gen = 0;                 // counts commits and releases: close notices one that slipped in while it waited
 };
 
 }  // namespace
@@ -65,8 +74,11 @@ ag_status ag_pager_create(int32_t num_pages, int32_t page_size, int32_t max_sess
 ag_status ag_pager_destroy(ag_pager* p)
 {
     if (!p) { set_error("pager is NULL"); return AG_ERR_INVALID_ARG; }
-    for (auto& s : p->sess)
+    for (auto& s : p->sess) {
         if (s.ev) { (void)hipEventSynchronize(s.ev); (void)hipEventDestroy(s.ev); }
+        for (auto& r : s.readers)
+            if (r.ev) { (void)hipEventSynchronize(r.ev); (void)hipEventDestroy(r.ev); }
+    }
     delete p;
     return AG_OK;
 }
@@ -79,6 +91,7 @@ ag_status ag_pager_open(ag_pager* p, int32_t* out)
         if (!p->sess[(size_t)s].open) {
             Session& x = p->sess[(size_t)s];
             x.open = true; x.reserved = 0; x.sealed = 0; x.pages.clear(); x.pending = false; x.ev_stream = nullptr;
+            for (auto& r : x.readers) r.pending = false;
             ++p->st.open_sessions;
             *out = s;
             return AG_OK;
@@ -90,29 +103,40 @@ ag_status ag_pager_open(ag_pager* p, int32_t* out)
 ag_status ag_pager_close(ag_pager* p, int32_t s)
 {
     if (!p) { set_error("pager is NULL"); return AG_ERR_INVALID_ARG; }
-    hipEvent_t wait_for = nullptr;
-    {
+    // The pages must not be reused while work that touches them may still run: the writer's last commit and
+    // every reader that released the session.  The waits happen outside the lock; a commit or release that
+    // arrives meanwhile (the generation moved) is waited for in another round.
+    for (;;) {
+        std::vector<hipEvent_t> wait_for;
+        uint64_t gen = 0;
+        {
+            std::lock_guard<std::mutex> lk(p->mu);
+            Session* x = find(p, s);
+            if (!x) return AG_ERR_INVALID_ARG;
+            if (x->pending) wait_for.push_back(x->ev);
+            for (auto& r : x->readers)
+                if (r.pending) wait_for.push_back(r.ev);
+            gen = x->gen;
+        }
+        for (hipEvent_t e : wait_for) {
+            ag_status st = hip_check(hipEventSynchronize(e), "hipEventSynchronize(close)");
+            if (st) return st;
+        }
         std::lock_guard<std::mutex> lk(p->mu);
         Session* x = find(p, s);
-        if (!x) return AG_ERR_INVALID_ARG;
-        if (x->pending) wait_for = x->ev;
+        if (!x) return AG_ERR_INVALID_ARG;             // closed by another thread meanwhile
+        if (x->gen != gen) continue;                   // something was committed or released while we waited
+        p->st.close_waits += (int64_t)wait_for.size();
+        for (auto it = x->pages.rbegin(); it != x->pages.rend(); ++it) {
+            p->owner[(size_t)*it] = -1;
+            p->free_list.push_back(*it);
+        }
+        x->pages.clear();
+        x->open = false; x->pending = false; x->reserved = x->sealed = 0;
+        for (auto& r : x->readers) r.pending = false;
+        --p->st.open_sessions;
+        return AG_OK;
     }
-    // outside the lock: the pages must not be reused while the last committed work may still touch them
-    if (wait_for) {
-        ag_status e = hip_check(hipEventSynchronize(wait_for), "hipEventSynchronize(close)");
-        if (e) return e;
-    }
-    std::lock_guard<std::mutex> lk(p->mu);
-    Session* x = find(p, s);
-    if (!x) return AG_ERR_INVALID_ARG;
-    for (auto it = x->pages.rbegin(); it != x->pages.rend(); ++it) {
-        p->owner[(size_t)*it] = -1;
-        p->free_list.push_back(*it);
-    }
-    x->pages.clear();
-    x->open = false; x->pending = false; x->reserved = x->sealed = 0;
-    --p->st.open_sessions;
-    return AG_OK;
 }
 
 ag_status ag_pager_reserve(ag_pager* p, int32_t s, int32_t n, int32_t* start_out)
@@ -175,6 +199,7 @@ ag_status ag_pager_commit(ag_pager* p, int32_t s, void* stream)
     x->ev_stream = (hipStream_t)stream;
     x->pending = true;
     x->sealed = x->reserved;
+    ++x->gen;
     ++p->st.commits;
     return AG_OK;
 }
@@ -200,6 +225,32 @@ ag_status ag_pager_acquire(ag_pager* p, int32_t s, void* stream, int32_t* sealed
     }
     if (wait) ++p->st.waits_issued; else ++p->st.waits_skipped;
     if (sealed_out) *sealed_out = x->sealed;
+    return AG_OK;
+}
+
+ag_status ag_pager_release(ag_pager* p, int32_t s, void* stream)
+{
+    if (!p) { set_error("pager is NULL"); return AG_ERR_INVALID_ARG; }
+    std::lock_guard<std::mutex> lk(p->mu);
+    Session* x = find(p, s);
+    if (!x) return AG_ERR_INVALID_ARG;
+    Session::Reader* r = nullptr;
+    for (auto& cand : x->readers)
+        if (cand.stream == (hipStream_t)stream) { r = &cand; break; }
+    if (!r) {
+        Session::Reader fresh;
+        fresh.stream = (hipStream_t)stream;
+        ag_status e = hip_check(hipEventCreateWithFlags(&fresh.ev, hipEventDisableTiming), "hipEventCreateWithFlags");
+        if (e) return e;
+        x->readers.push_back(fresh);
+        r = &x->readers.back();
+    }
+    // re-recording moves the event to the stream's newest work: one event per reader stream is enough
+    ag_status e = hip_check(hipEventRecord(r->ev, (hipStream_t)stream), "hipEventRecord(release)");
+    if (e) return e;
+    r->pending = true;
+    ++x->gen;
+    ++p->st.releases;
     return AG_OK;
 }
 
