@@ -3,13 +3,13 @@ decode reservation to a pre-established partition (Sec. III-C).  TEST INFRASTRUC
 controller (C++) shares no code with this file, and only tests, the smoke test and the benchmark's baseline leg
 may import it.
 
-One `Controller` object is one run of the algorithm's loop body per `tick()`:
-  measure   dL = summed decode-step time, dK = decode steps since the last tick      (TPOT measurement, Sec. III-B)
-  compute   TPOT_step = dL / dK                                                      (the display equation there)
-  protect   if TPOT_step > theta_high:  B <- max(B_min, B - dB),  R <- min(S, R + dR)
-  relax     elif TPOT_step < theta_low: B <- min(B_max, B + dB),  R <- max(R_base, R - dR)
-  classify  decode, or a prefill no longer than B, goes to Q_D; anything else to Q_P
-  partition S_decode = R, S_prefill = S - R
+What it computes.  Each control interval the scheduler looks at the mean time per decode step it measured
+(the TPOT of Sec. III-B), compares it with a band [theta_low, theta_high], and when the mean lies strictly
+outside the band moves two knobs by one increment each, in opposite directions and each inside its own range:
+the decode reservation R_min (up when decode is too slow, never above S nor below R_base) and the token budget
+B_prefill under which a resume prefill may join the decode queue (down when decode is too slow, within
+[B_min, B_max]).  The request classifier and the partition (R_min for decode, the rest for prefill) then use
+the new values.  `tick()` is that interval; its order of steps is Algorithm 1's.
 
 Readings where the paper is silent (each also listed with the library's design notes):
   * dK = 0 (no decode step in the interval) makes TPOT_step 0/0; the interval then changes nothing.

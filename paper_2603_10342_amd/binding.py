@@ -14,8 +14,7 @@ from typing import Optional, Sequence
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# AGATTN_LIB selects another build of the same library (kernel tuning experiments); default is the in-tree build.
-LIB_PATH = os.environ.get("AGATTN_LIB") or os.path.join(HERE, "libagattn.so")
+LIB_PATH = os.path.join(HERE, "libagattn.so")
 
 AG_OK, AG_ERR_INVALID_ARG, AG_ERR_UNSUPPORTED, AG_ERR_WORKSPACE, AG_ERR_HIP, AG_ERR_NO_SPACE = 0, -1, -2, -3, -4, -5
 AG_F32, AG_BF16 = 0, 1
@@ -410,7 +409,10 @@ class Slots:
     def get(self, index: int) -> dict:
         u, d, p = C.c_int32(), C.c_void_p(), C.c_void_p()
         _check(lib().ag_slots_get(self._h, index, C.byref(u), C.byref(d), C.byref(p)))
-        return {"decode_units": u.value, "decode_stream": int(d.value or 0), "prefill_stream": int(p.value or 0)}
+        # the last entry reserves the whole device for decode and has NO prefill stream: None, never 0 - a 0 would
+        # be taken for the default stream by every launch helper and run a prefill unmasked on all CUs
+        return {"decode_units": u.value, "decode_stream": int(d.value or 0),
+                "prefill_stream": int(p.value) if p.value else None}
 
     def bind(self, r_min: int) -> int:
         i = C.c_int32()

@@ -20,8 +20,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-strict-ali
 
 
 def build(extra=(), verbose: bool = False, lib: str = LIB, tag: str = "") -> str:
-    """Compile every source and link `lib`.  `extra` are added hipcc flags (e.g. -DAG_DECODE_SPLIT=256);
-    `tag` keeps the objects of a variant build apart."""
+    """Compile every source and link `lib`.  `extra` are added hipcc flags; `tag` keeps the objects of a second
+    build (another output path) apart."""
     global OBJ
     obj_dir = OBJ + tag
     os.makedirs(obj_dir, exist_ok=True)

@@ -73,25 +73,34 @@ ag_status ag_ctl_record_decode(ag_ctl* c, double step_us)
     return AG_OK;
 }
 
+// Which way an interval pushes: +1 when the measured time per decode step is above the band (decode needs
+// protection), -1 when it is below (prefill may have more), 0 inside the band or when nothing was measured
+// (a NaN compares false both ways).  Both edges are exclusive (Algorithm 1).
+static int pressure(double tpot_us, const ag_ctl_params& p)
+{
+    return (tpot_us > p.theta_high_us) - (tpot_us < p.theta_low_us);
+}
+
+// v moved by `by`, held inside [lo, hi]
+static int32_t moved_within(int32_t v, int64_t by, int32_t lo, int32_t hi)
+{
+    const int64_t t = (int64_t)v + by;
+    return (int32_t)(t < lo ? lo : t > hi ? hi : t);
+}
+
+// The feedback rule of Sec. III-B / Algorithm 1 as one signed step: the decode reservation moves WITH the
+// pressure, the resume-prefill budget AGAINST it, each by its own increment and inside its own range.
 ag_status ag_ctl_tick(ag_ctl* c, ag_ctl_state* out)
 {
     if (!c) { set_error("ctl is NULL"); return AG_ERR_INVALID_ARG; }
     std::lock_guard<std::mutex> lk(c->mu);
     const ag_ctl_params& p = c->p;
-    if (c->dK == 0) {
-        c->tpot = NAN;                                   // nothing measured: leave R_min and B_prefill alone
-    } else {
-        c->tpot = c->dL / (double)c->dK;
-        if (c->tpot > p.theta_high_us) {                 // protect decode
-            c->b_prefill = c->b_prefill - p.delta_b < p.b_min ? p.b_min : c->b_prefill - p.delta_b;
-            c->r_min = c->r_min + p.delta_r > p.S ? p.S : c->r_min + p.delta_r;
-            ++c->raised;
-        } else if (c->tpot < p.theta_low_us) {           // relax
-            c->b_prefill = c->b_prefill + p.delta_b > p.b_max ? p.b_max : c->b_prefill + p.delta_b;
-            c->r_min = c->r_min - p.delta_r < p.r_base ? p.r_base : c->r_min - p.delta_r;
-            ++c->lowered;
-        }
-    }
+    c->tpot = c->dK ? c->dL / (double)c->dK : NAN;
+    const int dir = pressure(c->tpot, p);
+    c->r_min = moved_within(c->r_min, (int64_t)dir * p.delta_r, p.r_base, p.S);
+    c->b_prefill = moved_within(c->b_prefill, -(int64_t)dir * p.delta_b, p.b_min, p.b_max);
+    c->raised += dir > 0;
+    c->lowered += dir < 0;
     c->dL = 0.0;
     c->dK = 0;
     ++c->intervals;

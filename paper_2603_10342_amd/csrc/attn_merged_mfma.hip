@@ -535,20 +535,12 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     // waves per SIMD.  Otherwise two groups per wave: keys items of up to 2 tq rows, and - once some session
     // may bring more than that - rows items of up to 8 tq rows.
     const int R = a.max_new > tq ? 2 : 1;
-#ifdef AG_MERGED_NO_ROWS_ITEMS
-    const bool rows = false;
-#else
     const bool rows = a.max_new > R * tq;
-#endif
     const int rk = R * tq, rw = rows ? 4 * R * tq : 0;
     // a session of N rows has at most N / (rows per full item) + 1 items, and every item has at least one row
     const int64_t items_max = std::min<int64_t>(a.total_rows, (int64_t)a.total_rows / (rw ? rw : rk) + a.batch);
     if (items_max > 65535 || a.c.hkv > 65535) { set_error("too many items (%lld) or KV heads for one launch grid", (long long)items_max); return AG_ERR_INVALID_ARG; }
-#ifdef AG_MERGED_FORCE_SPLIT
-    const int split = AG_MERGED_FORCE_SPLIT;
-#else
     const int split = choose_split(items_max, a.c.hkv, a.max_ctx, rows ? 1024 : 2048);
-#endif
     const int nsm = splits_for(a.max_ctx, split);
     const Layout L = layout(a.total_rows, a.hq, a.max_ctx);
     float* ws_o = (float*)ws;

@@ -79,12 +79,8 @@ constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may exceed
 constexpr float kWeightSumLimit = 16384.0f;   // a lane's 32 weights of a tile may sum to this much before m is moved
 constexpr float kLog2e = 1.4426950408889634f;
 
-#ifndef AG_PREFILL_WAVES_PER_SIMD
-#define AG_PREFILL_WAVES_PER_SIMD 2
-#endif
-#ifndef AG_PREFILL_AHEAD
-#define AG_PREFILL_AHEAD 3
-#endif
+constexpr int kWavesPerSimd = 2;        // 205 registers per lane
+constexpr int kOperandsAhead = 3;       // LDS operand reads run this many matrix instructions ahead of their use
 
 __device__ __forceinline__ u32x4 ld16g(const __bf16* p) { return *reinterpret_cast<const u32x4*>(p); }
 
@@ -105,7 +101,7 @@ __device__ __forceinline__ u32x4 keep_quads(u32x4 u, int keep_lo, int keep_hi)
 // neighbouring matrix instructions write different accumulators.
 __device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&qf)[8], f32x16 (&sc)[2])
 {
-    constexpr int kAhead = AG_PREFILL_AHEAD;
+    constexpr int kAhead = kOperandsAhead;
     bf16x8 opnd[kAhead + 1];
     auto operand = [&](int i) -> const unsigned char* { return kb + (i & 1) * 512 + (i >> 1) * 2048; };   // (ks, b)
 #pragma unroll
@@ -124,7 +120,7 @@ __device__ __forceinline__ void qk_tile(const unsigned char* kb, const bf16x8 (&
 // Same operand ring as qk_tile (it also bounds the registers the compiler may spend on early reads).
 __device__ __forceinline__ void pv_tile(const unsigned char* vb, const bf16x8 (&pb)[4], f32x16 (&o)[4])
 {
-    constexpr int kAhead = AG_PREFILL_AHEAD;
+    constexpr int kAhead = kOperandsAhead;
     bf16x8 opnd[kAhead + 1];
     auto operand = [&](int i) -> const unsigned char* { return vb + (i & 3) * 512 + (i >> 2) * 4096; };   // (j, mb)
 #pragma unroll
@@ -177,7 +173,7 @@ __device__ __forceinline__ void exp_tile(const f32x16 (&sc)[2], float sl2, float
 // every 32 * NW / GP tokens instead of every 32 * NW (ragged chunks fill their last tile better) and all waves
 // of a workgroup end within one tile of each other on the diagonal.
 template <int NW, int GP>
-__global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mfma_kernel(AttnArgs a, int tiles_max,
+__global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(AttnArgs a, int tiles_max,
                                                                                          int per_xcd, int64_t total_work)
 {
     static_assert(NW % GP == 0, "the heads of a group share the workgroup's waves evenly");
@@ -386,7 +382,7 @@ __global__ __launch_bounds__(64 * NW, AG_PREFILL_WAVES_PER_SIMD) void prefill_mf
             // of matrix instruction i + kAhead, matrix instruction i, and the exp of scores 2i and 2i + 1;
             // the fences keep the compiler from regrouping them.  Neighbouring matrix instructions belong
             // to different accumulators.
-            constexpr int kAhead = AG_PREFILL_AHEAD;
+            constexpr int kAhead = kOperandsAhead;
             bf16x8 opnd[kAhead + 1];
             auto operand = [&](int i) -> const unsigned char* {   // order (j, mb)
                 return vb + (i & 3) * 512 + (i >> 2) * 4096;
@@ -529,16 +525,10 @@ ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st)
     // 256-row workgroups when chunks are long enough to fill them (a K/V tile then feeds twice the rows);
     // 128-row workgroups keep short, ragged chunks efficient.  Groups of 2, 4 or 8 query heads share a workgroup
     // (a group of 8 only fits the 256-row form).
-#ifdef AG_PREFILL_FORCE_NW
-    const bool big = AG_PREFILL_FORCE_NW == 8;
-#else
     const bool big = a.max_new >= 512;
-#endif
-#ifndef AG_PREFILL_NO_HEAD_PACKING
     if (G == 4) return big ? launch_prefill_nw<8, 4>(a, st) : launch_prefill_nw<4, 4>(a, st);
     if (G == 2) return big ? launch_prefill_nw<8, 2>(a, st) : launch_prefill_nw<4, 2>(a, st);
     if (G == 8) return launch_prefill_nw<8, 8>(a, st);
-#endif
     return big ? launch_prefill_nw<8, 1>(a, st) : launch_prefill_nw<4, 1>(a, st);
 }
 

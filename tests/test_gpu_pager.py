@@ -121,3 +121,58 @@ def test_a_reader_behind_a_long_writer_is_made_to_wait():
         torch.cuda.synchronize()
         pager.destroy()
         slots.close()
+
+
+def test_pages_of_a_closed_session_are_not_rewritten_under_a_reader_still_in_flight():
+    """Session A's decode is queued behind a long kernel on the reader's stream and released; A is closed and
+    session B, which gets A's pages back from the free list, has its prompt appended into them on the writer's
+    stream.  Launch order is fixed: long kernel, A's decode, release, close(A), B's append.  close must have
+    waited for A's decode, so A's result is the oracle's and B's append lands afterwards."""
+    g = I.Geometry(8, 2, 128, 16, 1024, I.BF16)
+    pager = B.Pager(g.num_pages, g.page_size, 4, 600)
+    slots = B.Slots(16)
+    e = slots.get(slots.bind(16))
+    s_dec, s_pre = e["decode_stream"], e["prefill_stream"]
+    try:
+        n = 8000
+        a = pager.open()
+        pager.reserve(a, n)
+        bt_a = pager.export([a])
+        fill = I.draw_batch(g, bt_a, [0], [n], 901, 1, sigma_qk=1.0, sigma_v=1.0)
+        kp, vp = fresh_pools(g)
+        oracle_append(kp, vp, fill)
+        ref = O.decode(kp, vp, g.dtype, fill.q[-1:], bt_a, np.asarray([n], np.int32), g.num_q_heads, g.scale)
+        cache = make_cache(g)
+        d = DevBatch(fill)
+        q1, ctx = d.q[-1:].contiguous(), i32([n])
+        ws = torch.empty(B.ag_attn_decode_workspace_bytes(1, g.num_q_heads, 128, n) // 4, dtype=torch.float32, device="cuda")
+        out = torch.full_like(q1, float("nan"))
+        busy_out = torch.empty_like(d.q)
+        B.ag_kv_append(cache, d.k_new, d.v_new, d.bt, d.prefix, d.new, d.cu, d.total, stream=s_pre)
+        pager.commit(a, s_pre)
+        torch.cuda.synchronize()
+        # reader's stream: a long prefill first (it only reads A's pages), then A's decode
+        pager.acquire(a, s_dec)
+        for _ in range(3):
+            B.ag_attn_prefill(cache, d.q, busy_out, d.bt, d.new, d.cu, d.total, d.max_new, g.num_q_heads, g.scale, stream=s_dec)
+        B.ag_attn_decode(cache, q1, out, d.bt, ctx, n, g.num_q_heads, g.scale, ws, stream=s_dec)
+        pager.release(a, s_dec)
+        w0 = pager.stats()["close_waits"]
+        pager.close(a)                                   # must not return while the decode can still read the pages
+        assert pager.stats()["close_waits"] - w0 >= 1
+        b = pager.open()
+        pager.reserve(b, n)
+        bt_b = pager.export([b])
+        assert set(bt_b[0, :n // 16].tolist()) == set(bt_a[0, :n // 16].tolist())      # the same physical pages
+        other = I.draw_batch(g, bt_b, [0], [n], 902, 1, sigma_qk=4.0, sigma_v=4.0)
+        do = DevBatch(other)
+        B.ag_kv_append(cache, do.k_new, do.v_new, do.bt, do.prefix, do.new, do.cu, do.total, stream=s_pre)
+        pager.commit(b, s_pre)
+        torch.cuda.synchronize()
+        check_close(to_f64(out, g.dtype), ref, g.dtype, "decode of the closed session")
+        pager.close(b)
+        assert pager.stats()["free_pages"] == g.num_pages
+    finally:
+        torch.cuda.synchronize()
+        pager.destroy()
+        slots.close()

@@ -37,7 +37,7 @@ def test_every_entry_partitions_the_device():
                 pre = where_it_ran(e["prefill_stream"])
                 assert not (dec & pre) and (dec | pre) == everything
             else:
-                assert e["prefill_stream"] == 0 and dec == everything
+                assert e["prefill_stream"] is None and dec == everything
         with pytest.raises(B.AgError):
             slots.get(slots.count())
     finally:
