@@ -1,7 +1,8 @@
 """The KV page manager (paper Sec. III-C, memory management) without a device: the free list, all-or-nothing
 reservations, read-only marking, rows, and many threads at once.  Which physical page a session receives is
 the manager's choice; the tests check what must hold whichever it chooses (disjoint ownership, conservation,
-order of logical pages), against a model kept beside it in plain Python sets."""
+order of logical pages).  The random walk against the plain model of the bookkeeping (oracle/pager_model.py)
+is in tests/test_pager_model_pins.py."""
 import random
 import threading
 
@@ -101,56 +102,6 @@ def test_bad_arguments():
     l = B.lib()
     assert l.ag_pager_open(None, None) == B.AG_ERR_INVALID_ARG and l.ag_pager_destroy(None) == B.AG_ERR_INVALID_ARG
     assert B.ag_status_string(B.AG_ERR_NO_SPACE) == "AG_ERR_NO_SPACE"
-    p.destroy()
-
-
-def test_random_walk_against_a_set_model():
-    rnd = random.Random(10342)
-    P, ps, S, row = 200, 16, 12, 24
-    p = B.Pager(P, ps, S, row)
-    model = {}                                         # session -> [reserved, sealed, n_pages]
-    for step in range(4000):
-        op = rnd.random()
-        if op < 0.15 and len(model) < S:
-            s = p.open()
-            assert s not in model
-            model[s] = [0, 0, 0]
-        elif op < 0.25 and model:
-            s = rnd.choice(list(model))
-            p.close(s)
-            del model[s]
-        elif op < 0.8 and model:
-            s = rnd.choice(list(model))
-            n = rnd.choice([0, 1, 1, 5, 16, 17, 100])
-            need = -(-(model[s][0] + n) // ps)
-            free = P - sum(m[2] for m in model.values())
-            if need <= row and need - model[s][2] <= free:
-                assert p.reserve(s, n) == model[s][0]
-                model[s][0] += n
-                model[s][2] = max(model[s][2], need)
-            else:
-                with pytest.raises(B.AgError):
-                    p.reserve(s, n)
-        elif model:
-            s = rnd.choice(list(model))
-            p.seal(s)
-            model[s][1] = model[s][0]
-        if step % 97 == 0 or step == 3999:
-            owned = {}
-            for s, (res, sealed, npg) in model.items():
-                assert p.lengths(s) == {"reserved": res, "sealed": sealed, "pages": npg}
-                for i, pg in enumerate(pages_of(p, s)):
-                    assert pg not in owned                              # no page in two rows, or twice in one
-                    owned[pg] = (s, i)
-            st = p.stats()
-            assert st["free_pages"] == P - len(owned) and st["open_sessions"] == len(model)
-            for pg in range(P):
-                state = p.page_state(pg)
-                if pg not in owned:
-                    assert state == B.AG_PAGE_FREE
-                else:
-                    s, i = owned[pg]
-                    assert state == (B.AG_PAGE_SEALED if (i + 1) * ps <= model[s][1] else B.AG_PAGE_WRITABLE)
     p.destroy()
 
 
