@@ -74,7 +74,11 @@ constexpr int kKStages = 3;             // K(t+2) is requested while K(t) is use
 // supported by the loop but measured no faster, so both workgroup shapes use 80 KiB: two 4-wave workgroups or
 // one 8-wave workgroup per CU.
 constexpr int v_stages(int) { return 2; }
-constexpr int lds_bytes(int nw) { return (kKStages + v_stages(nw)) * kTile; }
+// The 8-wave form also keeps two windows of 64 page ids (16 key tiles each) of the session's block-table row in
+// LDS, see the kernel; the 4-wave form has no room for them (two workgroups of 80 KiB fill a CU's LDS).
+constexpr int kIdWindow = 64;
+constexpr bool ids_in_lds(int nw) { return nw == 8; }
+constexpr int lds_bytes(int nw) { return (kKStages + v_stages(nw)) * kTile + (ids_in_lds(nw) ? 2 * kIdWindow * 4 : 0); }
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row's maximum may exceed m when the ordered path leaves m alone
 constexpr float kWeightSumLimit = 16384.0f;   // a lane's 32 weights of a tile may sum to this much before m is moved
 constexpr float kLog2e = 1.4426950408889634f;
@@ -272,19 +276,40 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     const int kpg = lane >> 4, kslot = lane & 15;           // K: lane = key of the tile (page, slot)
     const int kmask[4] = {kpg == 0 ? -1 : 0, kpg == 1 ? -1 : 0, kpg == 2 ? -1 : 0, kpg == 3 ? -1 : 0};
 
-    // Physical pages of a tile, through scalar loads (the index is uniform), fetched one iteration before the
-    // tile's data is requested, so no data request ever waits for a block-table read.
-    struct Pages { int k[4]; int v; };
+    // Physical pages of a tile.  Scalar form (the prologue, and the 4-wave kernel throughout): scalar loads (the
+    // index is uniform), fetched one iteration before the tile's data is requested.  A scalar load in flight
+    // costs more than its latency, though: it shares a counter with the LDS operand reads and returns out of
+    // order, so while one is pending every wait for an operand becomes a wait for everything.  The 8-wave
+    // kernel therefore keeps the ids in LDS: wave 0 brings the session's block-table row in windows of 64
+    // pages (16 key tiles) by one direct load each, two windows resident, and every lane reads the id it needs
+    // (its own page of the K tile, the wave's page of the V tile) with an ordinary LDS read.
+    constexpr bool kLdsIds = ids_in_lds(NW);
+    struct Pages { int k; int v; };                            // k: this LANE's page of the K tile; v: the wave's page of the V tile
     const int v_page = (wu * kPer) / 4;                        // page of a V tile this wave brings in (4 runs per page)
-    auto pages_of = [&](int tk, int tv, Pages& pg) {
+    auto pages_scalar = [&](int tk, int tv, Pages& pg) {
+        int pid[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) pg.k[i] = bt[min(tk * 4 + i, last_page)];
+        for (int i = 0; i < 4; ++i) pid[i] = bt[min(tk * 4 + i, last_page)];
+        // this lane's page among the four (uniform) ids, by masks: a chain of ?: here compiles to branches
+        pg.k = (pid[0] & kmask[0]) | (pid[1] & kmask[1]) | (pid[2] & kmask[2]) | (pid[3] & kmask[3]);
         pg.v = bt[min(tv * 4 + v_page, last_page)];
     };
+    const int32_t* const id_lds = reinterpret_cast<const int32_t*>(lds + (kKStages + kVStages) * kTile);
+    // window w = logical pages [64 w, 64 w + 64), clamped to the session's last page, into slot w & 1
+    auto refill_ids = [&](int win) {
+        const int lp = min(win * kIdWindow + lane, last_page);
+        load_dword_to_lds(a.bt + (int64_t)s * a.max_pages + lp, lds_address(id_lds) + (win & 1) * (kIdWindow * 4));
+    };
+    auto pages_of = [&](int tk, int tv, Pages& pg) {
+        if constexpr (kLdsIds) {
+            pg.k = id_lds[(tk * 4 + kpg) & (2 * kIdWindow - 1)];
+            pg.v = __builtin_amdgcn_readfirstlane(id_lds[(tv * 4 + v_page) & (2 * kIdWindow - 1)]);
+        } else {
+            pages_scalar(tk, tv, pg);
+        }
+    };
     // K(tk): instruction i of wave w moves chunk c = kPer*w + i of all 64 keys: four 256-byte runs, one per page.
-    auto request_k = [&](int tk, const int (&pid)[4]) {
-        // this lane's page among the four (uniform) ids, by masks: a chain of ?: here compiles to branches
-        const int mine = (pid[0] & kmask[0]) | (pid[1] & kmask[1]) | (pid[2] & kmask[2]) | (pid[3] & kmask[3]);
+    auto request_k = [&](int tk, int mine) {
         const unsigned char* src = (const unsigned char*)kpool + ((int64_t)mine * hkv + g) * (int64_t)(D * PS * 2) +
                                    (wu * kPer) * 256 + kslot * 16;
         const unsigned dst = lds_address(k_lds) + (tk % kKStages) * kTile + (wu * kPer) * 1024;
@@ -328,17 +353,20 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     const unsigned char* const k_lane = k_lds + n * 16 + hi * 1024;
     const unsigned char* const v_lane = v_lds + n * 16 + hi * 2048;
 
-    // ---- prologue: K(0), K(1) requested and landed ----
+    // ---- prologue: K(0), K(1) requested and landed (and the first window of page ids) ----
     Pages pg;
-    pages_of(0, 0, pg);
+    if constexpr (kLdsIds) {
+        if (wu == 0) refill_ids(0);
+    }
+    pages_scalar(0, 0, pg);
     request_k(0, pg.k);
-    pages_of(min(1, n_tiles - 1), 0, pg);
+    pages_scalar(min(1, n_tiles - 1), 0, pg);
     request_k(1, pg.k);
     if (kVLead) {                                    // V(0) too when iteration t requests V(t + 1)
-        pages_of(0, 0, pg);
+        pages_scalar(0, 0, pg);
         request_v(0, pg.v);
     }
-    pages_of(min(2, n_tiles - 1), min(kVLead, n_tiles - 1), pg);   // what iteration 0 requests: V(kVLead) and K(2)
+    pages_scalar(min(2, n_tiles - 1), min(kVLead, n_tiles - 1), pg);   // what iteration 0 requests: V(kVLead) and K(2)
     AG_WAIT_VMCNT(0);
     __syncthreads();
     f32x16 sc[2];
@@ -352,10 +380,17 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     // does not need are skipped.
     auto iter = [&](int t, bf16x8 (&p_prev)[4], bf16x8 (&p_cur)[4]) {
         const int tv = min(t, n_tiles - 1);          // the V tile that must have landed when this iteration ends
-        Pages nxt;                                    // ids for the next iteration's requests
-        pages_of(min(t + 3, n_tiles - 1), min(t + 1 + kVLead, n_tiles - 1), nxt);
+        if constexpr (kLdsIds) {
+            // The window holding tile t + 4 comes in one iteration before its first id is read (iteration t + 1
+            // reads those of K(t + 4)); issued ahead of this iteration's tile requests, it has landed when wave 0
+            // passes the wait at the end of the iteration, and the barrier there shows it to the other waves.
+            // The slot it replaces holds the window two back, which nothing reads any more.
+            if (wu == 0 && ((t + 4) & 15) == 0) refill_ids((t + 4) >> 4);
+        }
         request_v((t + kVLead) % kVStages, pg.v);
         request_k(t + 2, pg.k);
+        Pages nxt;                                    // ids for the next iteration's requests
+        pages_of(min(t + 3, n_tiles - 1), min(t + 1 + kVLead, n_tiles - 1), nxt);
         const bool do_sm = t < wave_tiles, do_pv = t >= 1 && t <= wave_tiles;
         const unsigned char* kb = k_lane + (t % kKStages) * kTile;
         const unsigned char* vb = v_lane + ((t + kVStages - 1) % kVStages) * kTile;   // V(t-1)

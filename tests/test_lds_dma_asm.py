@@ -36,7 +36,7 @@ def test_m0_belongs_to_the_direct_loads_only(src, tmp_path):
         if not code or code.startswith(".") or code.endswith(":"):
             continue
         ins.append(code)
-    loads = [i for i, c in enumerate(ins) if c.startswith("global_load_lds_dwordx4")]
+    loads = [i for i, c in enumerate(ins) if c.startswith("global_load_lds_dword")]     # the 16-byte and the 4-byte form
     assert len(loads) >= 8, "the direct loads are gone from the generated code?"
     for i in loads:
         assert re.match(r"s_mov_b32 m0, ", ins[i - 1]), (ins[i - 2:i + 1])
