@@ -203,14 +203,22 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     const int g = (int)(wk / per_head);
     const int rem = (int)(wk % per_head);
     const int j = rem / hpw;                        // tile index among the KV head's tiles
-    int s = -1, qt = 0, N = 0;
+    int s = -1, qt = 0, N = 0, P = 0, row0 = 0;
     {
         const int ln = threadIdx.x & 63;
         int before = 0;                             // tiles of the sessions of earlier passes
         for (int s0 = 0; s0 < a.batch && s < 0; s0 += 256) {
-            int lens[4];                            // four passes' lengths are fetched together
+            // four passes' lengths are fetched together, and with them the prefix length and the row offset of
+            // every session: whichever session the tile turns out to belong to, no second round trip follows
+            int lens[4], pre[4], cu[4];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) lens[k] = s0 + 64 * k + ln < a.batch ? a.new_lens[s0 + 64 * k + ln] : 0;
+            for (int k = 0; k < 4; ++k) {
+                const int ss = s0 + 64 * k + ln;
+                const bool in = ss < a.batch;
+                lens[k] = in ? a.new_lens[ss] : 0;
+                pre[k] = in && a.prefix_lens ? a.prefix_lens[ss] : 0;
+                cu[k] = in ? a.cu_new[ss] : 0;
+            }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (s >= 0) break;                  // uniform
@@ -228,6 +236,8 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
                     const int l = __builtin_ctzll(hit);              // first session whose tiles reach past j
                     s = s0 + 64 * k + l;
                     N = __builtin_amdgcn_readlane(len, l);
+                    P = __builtin_amdgcn_readlane(pre[k], l);
+                    row0 = __builtin_amdgcn_readlane(cu[k], l);
                     qt = before + __builtin_amdgcn_readlane(incl, l) - 1 - j;   // the session's tiles, longest first
                 }
                 before += pass_total;
@@ -236,9 +246,8 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     }
     if (s < 0) return;                              // beyond the batch's tiles
     const int q0 = qt * BM;
-    const int P = a.prefix_lens ? a.prefix_lens[s] : 0;
     const int ctx = P + N;
-    const int64_t t_base = (int64_t)a.cu_new[s] + q0;
+    const int64_t t_base = (int64_t)row0 + q0;
 
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
     const int wu = __builtin_amdgcn_readfirstlane(w);           // the same value, known to be uniform: used only
@@ -303,7 +312,7 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     auto pages_of = [&](int tk, int tv, Pages& pg) {
         if constexpr (kLdsIds) {
             pg.k = id_lds[(tk * 4 + kpg) & (2 * kIdWindow - 1)];
-            pg.v = __builtin_amdgcn_readfirstlane(id_lds[(tv * 4 + v_page) & (2 * kIdWindow - 1)]);
+            pg.v = id_lds[(tv * 4 + v_page) & (2 * kIdWindow - 1)];      // uniform; made scalar where it is used
         } else {
             pages_scalar(tk, tv, pg);
         }
@@ -319,7 +328,8 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
     // V(tv): a page's [half][channel][8 keys] layout is the LDS layout, so a V tile is sixteen 1 KiB runs;
     // wave w moves runs kPer*w .. kPer*w + kPer - 1, all of page v_page.
     constexpr int v_runs_per_page = 4;
-    auto request_v = [&](int stage, int pid) {
+    auto request_v = [&](int stage, int pid_any_lane) {
+        const int pid = __builtin_amdgcn_readfirstlane(pid_any_lane);
         const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) +
                                    ((wu * kPer) % v_runs_per_page) * 1024 + lane * 16;
         const unsigned dst = lds_address(v_lds) + stage * kTile + (wu * kPer) * 1024;
