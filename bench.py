@@ -9,7 +9,8 @@ Prints ONE JSON line.  The headline metric is decode-attention HBM GB/s on the
 decode-only configuration (64 sessions, contexts U[1024, 4096], 32/8 heads,
 head_dim 128, page 16, bf16).  A step is one pass of the decode path over the
 batch: ag_kv_append of the step's token for every session, then
-ag_attn_decode.  The same line carries the two prefill configurations
+ag_attn_decode.  (ag_decode_step, the same step in one launch, is timed beside
+it.)  The same line carries the two prefill configurations
 (TFLOP/s against the dense bf16 MFMA peak), the mixed-load decode-step
 percentiles under CU-masked streams, and the fp64 oracle timed on the host.
 
@@ -40,10 +41,14 @@ def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
+TRAFFIC_FILE = os.path.join("profiles", "hbm_traffic_pmc.txt")
+
+
 def measured_traffic(key):
     """HBM bytes per launch (read + write) that rocprofv3's FETCH_SIZE / WRITE_SIZE counters showed for a kernel on a
-    workload, from the committed summary profiles/hbm_traffic_pmc.txt (PMC runs cannot be taken inside this script)."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_pmc.txt")
+    workload.  NOT measured in this run: counter runs cannot be taken inside this script, so the figure is read
+    from the committed summary profiles/hbm_traffic_pmc.txt (see traffic_source())."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     if not os.path.exists(path):
         return None
     for line in open(path):
@@ -51,6 +56,22 @@ def measured_traffic(key):
         if len(f) == 3 and f[0] == key:
             return int(f[1]) + int(f[2])
     return None
+
+
+def traffic_source():
+    """Where `traffic` comes from: the summary file and the library commit it was taken at (its first line)."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
+    if not os.path.exists(path):
+        return None
+    first = open(path).readline().strip().lstrip("# ")
+    return f"{TRAFFIC_FILE} ({first}); a separate rocprofv3 --pmc run, not this run"
+
+
+def roofline(bound, achieved, peak, unit, key, **extra):
+    r = {"bound": bound, "achieved": achieved, "peak": peak, "unit": unit, "frac": achieved / peak,
+         "traffic": measured_traffic(key), "traffic_source": traffic_source()}
+    r.update(extra)
+    return r
 
 
 def pct(xs, p):
@@ -145,6 +166,8 @@ def bench_decode(args, torch, B, I):
         sets.append((cache, btd))
     ws = torch.empty(B.ag_attn_decode_workspace_bytes(nb, g.num_q_heads, g.head_dim, max_ctx) // 4,
                      dtype=torch.float32, device="cuda")
+    ws_step = torch.zeros(B.ag_decode_step_workspace_bytes(nb, g.num_q_heads, g.head_dim, max_ctx) // 4,
+                          dtype=torch.float32, device="cuda")          # zeroed once; every call leaves its counters zero
     torch.cuda.synchronize()
 
     def one(i):
@@ -152,21 +175,26 @@ def bench_decode(args, torch, B, I):
         B.ag_kv_append(cache, step.k_new, step.v_new, btd, step.prefix, step.new, step.cu, step.total)
         B.ag_attn_decode(cache, step.q, step.out, btd, ctx, max_ctx, g.num_q_heads, g.scale, ws)
 
+    def one_launch(i):
+        cache, btd = sets[i % len(sets)]
+        B.ag_decode_step(cache, step.k_new, step.v_new, step.q, step.out, btd, ctx, max_ctx, g.num_q_heads, g.scale, ws_step)
+
     sec = time_steps(torch, one, args.steps, args.warmup)
     prof = kernel_time(B, torch, one, args.steps, args.warmup)
-    sec_graph = None
-    if args.graph:
-        # the same step recorded once per session set into a HIP graph and replayed
-        graphs = []
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        for r in range(len(sets)):
-            gr = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(gr, stream=side):
-                one(r)
-            graphs.append(gr)
-        torch.cuda.synchronize()
-        sec_graph = time_steps(torch, lambda i: graphs[i % len(graphs)].replay(), args.steps, args.warmup)
+    sec_one = time_steps(torch, one_launch, args.steps, args.warmup)
+    prof_one = kernel_time(B, torch, one_launch, args.steps, args.warmup)
+    # the same step recorded once per session set into a HIP graph and replayed
+    graphs = []
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    for r in range(len(sets)):
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr, stream=side):
+            one(r)
+        graphs.append(gr)
+    torch.cuda.synchronize()
+    sec_graph = time_steps(torch, lambda i: graphs[i % len(graphs)].replay(), args.steps, args.warmup)
+    del graphs
 
     esz = 2
     kv_bytes = int(c.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
@@ -174,17 +202,39 @@ def bench_decode(args, torch, B, I):
     bt_bytes = int(((c.ctx_lens + g.page_size - 1) // g.page_size).sum()) * 4
     attn_bytes = kv_bytes + qo_bytes + bt_bytes
     append_bytes = 2 * nb * g.kv_bytes_per_token
+    step_bytes = attn_bytes + append_bytes
     out = {
         "ms_per_step": sec * 1e3,
-        "step_GBps": (attn_bytes + append_bytes) / sec / 1e9,
-        "attn_bytes": attn_bytes, "append_bytes": append_bytes, "kv_bytes": kv_bytes,
-        "kernel": "decode_split_kernel", "kernel_us": prof["mean_us"], "kernel_us_min": prof["min_us"],
+        "step_GBps": step_bytes / sec / 1e9,
+        "attn_bytes": attn_bytes, "append_bytes": append_bytes, "kv_bytes": kv_bytes, "step_bytes": step_bytes,
+        "entry_points": "ag_kv_append + ag_attn_decode (three launches)",
+        "kernel": "decode_split_kernel + decode_merge_kernel (the whole ag_attn_decode call)",
+        "kernel_us": prof["mean_us"], "kernel_us_min": prof["min_us"],
         "kernel_GBps": attn_bytes / (prof["mean_us"] * 1e-6) / 1e9,
+        "graph_replay_ms_per_step": sec_graph * 1e3, "graph_replay_step_GBps": step_bytes / sec_graph / 1e9,
+        "one_launch": {"entry_point": "ag_decode_step (append + attention + merge in one launch)",
+                       "ms_per_step": sec_one * 1e3, "step_GBps": step_bytes / sec_one / 1e9,
+                       "kernel_us": prof_one["mean_us"], "kernel_GBps": step_bytes / (prof_one["mean_us"] * 1e-6) / 1e9},
         "sets": len(sets), "sessions": nb, "mean_ctx": float(c.ctx_lens.mean()),
     }
-    if sec_graph is not None:
-        out["graph_replay_ms_per_step"] = sec_graph * 1e3
-        out["graph_replay_step_GBps"] = (attn_bytes + append_bytes) / sec_graph / 1e9
+    # the paper's own regime is a handful of agents (Sec. IV: 3-6 concurrent sessions): the step is then bound by
+    # its launches, not by bytes - the same two ways on 4 sessions of about 1000 tokens
+    gs = I.slm_geometry(1024)
+    small = I.make_decode(batch=4, lo=1000, hi=1100, num_pages=1024, geom=gs, seed=I.config_seed(2) + 7)
+    sf, ss = Dev(small.fill, torch), Dev(small.step, torch)
+    cache0 = B.KVCache(gs.num_pages, gs.page_size, gs.num_kv_heads, gs.head_dim, gs.dtype, fill=0.0)
+    B.ag_kv_append(cache0, sf.k_new, sf.v_new, sf.bt, sf.prefix, sf.new, sf.cu, sf.total)
+    smax = int(small.ctx_lens.max())
+
+    def small_two(i):
+        B.ag_kv_append(cache0, ss.k_new, ss.v_new, ss.bt, ss.prefix, ss.new, ss.cu, ss.total)
+        B.ag_attn_decode(cache0, ss.q, ss.out, ss.bt, ss.ctx, smax, g.num_q_heads, g.scale, ws)
+
+    def small_one(i):
+        B.ag_decode_step(cache0, ss.k_new, ss.v_new, ss.q, ss.out, ss.bt, ss.ctx, smax, g.num_q_heads, g.scale, ws_step)
+
+    out["four_sessions_of_1000_tokens"] = {"two_calls_us": time_steps(torch, small_two, args.steps, args.warmup) * 1e6,
+                                           "one_launch_us": time_steps(torch, small_one, args.steps, args.warmup) * 1e6}
     log("decode", json.dumps(out))
 
     if not args.no_cpu_baseline:
@@ -248,26 +298,29 @@ def bench_prefill(kind, args, torch, B, I):
         "flops": flops, "tokens": b.total_new, "sessions": b.batch,
         "kernel": "prefill_mfma_kernel", "kernel_us": prof["mean_us"], "kernel_us_min": prof["min_us"],
         "kernel_TFLOPs": flops / (prof["mean_us"] * 1e-6) / 1e12,
-        "roofline": {"bound": "mfma", "achieved": flops / (prof["mean_us"] * 1e-6) / 1e12,
-                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": flops / (prof["mean_us"] * 1e-6) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": measured_traffic("prefill_mfma_kernel." + ("config3" if kind == "cold" else "config4"))},
+        "roofline": roofline("mfma", flops / (prof["mean_us"] * 1e-6) / 1e12, MFMA_BF16_PEAK_TFLOPS, "TFLOP/s",
+                             "prefill_mfma_kernel." + ("config3" if kind == "cold" else "config4"),
+                             kernel="prefill_mfma_kernel", kernel_us=prof["mean_us"], algorithmic_flops=flops),
     }
     log(kind, json.dumps(out))
 
-    if kind == "cold" and not args.no_cpu_baseline:
+    if not args.no_cpu_baseline:
+        # the oracle on a bounded, seeded sample of query rows (all 32 heads of each), timed; the same rows of the
+        # GPU output are compared with it
         from oracle import oracle as O       # cpu_baseline leg
         kp, vp = I.zero_pool(g.pool_shape, g.dtype), I.zero_pool(g.pool_shape, g.dtype)
-        O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
-        rng = I.rng_for(I.config_seed(3), 77)
-        n_rows = 8192
+        fills = [b] if kind == "cold" else [c.fill, b]
+        for x in fills:
+            O.kv_append(kp, vp, g.dtype, x.k_new, x.v_new, x.block_tables, x.prefix_lens, x.new_lens, x.cu_new)
+        rng = I.rng_for(I.config_seed(3 if kind == "cold" else 4), 77)
+        n_rows = 8192 if kind == "cold" else 3072          # about 10 s of host time either way
         rs = rng.integers(0, b.batch, size=n_rows).astype(np.int32)
-        ri = rng.integers(0, 4096, size=n_rows).astype(np.int32)
+        ri = (rng.random(n_rows) * b.new_lens[rs]).astype(np.int32)
         t0 = time.perf_counter()
         ref = O.attn(kp, vp, g.dtype, b.q, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new, g.num_q_heads,
                      g.scale, rows=(rs, ri))
         t_cpu = time.perf_counter() - t0
-        fl = 4 * g.head_dim * g.num_q_heads * int((ri.astype(np.int64) + 1).sum())
+        fl = 4 * g.head_dim * g.num_q_heads * int((b.prefix_lens[rs].astype(np.int64) + ri + 1).sum())
         one(0)
         torch.cuda.synchronize()
         rows = torch.from_numpy(b.cu_new[rs].astype(np.int64) + ri).to("cuda")
@@ -276,8 +329,9 @@ def bench_prefill(kind, args, torch, B, I):
         out["cpu_baseline"] = {"value": fl / t_cpu / 1e12, "unit": "TFLOP/s", "cores": O.num_threads(),
                                "kind": "oracle", "sample": f"{n_rows} random query rows x 32 heads, {t_cpu:.1f} s"}
         out["check_vs_oracle"] = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
-                                  "rel_fro": float(np.linalg.norm(got - ref) / np.linalg.norm(ref))}
-        log("cold cpu", json.dumps(out["cpu_baseline"]), json.dumps(out["check_vs_oracle"]))
+                                  "rel_fro": float(np.linalg.norm(got - ref) / np.linalg.norm(ref)), "rows": n_rows}
+        log(kind + " cpu", json.dumps(out["cpu_baseline"]), json.dumps(out["check_vs_oracle"]))
+        del kp, vp
     return out
 
 
@@ -310,21 +364,18 @@ class MixedLoad:
         for f in (rfill, dfill):
             B.ag_kv_append(cache, f.k_new, f.v_new, f.bt, f.prefix, f.new, f.cu, f.total)
         self.max_ctx = self.dec.max_ctx
-        self.ws = torch.empty(B.ag_attn_decode_workspace_bytes(self.dec.b.batch, g.num_q_heads, g.head_dim, self.max_ctx) // 4,
+        self.ws = torch.zeros(B.ag_decode_step_workspace_bytes(self.dec.b.batch, g.num_q_heads, g.head_dim, self.max_ctx) // 4,
                               dtype=torch.float32, device="cuda")
         torch.cuda.synchronize()
         self.prefill_tokens = self.cold.total + self.res.total
         self.prefill_flops = m.cold.attn_flops() + m.resume.attn_flops()
         self.kv_bytes = int(m.decode.ctx_lens.astype(np.int64).sum()) * g.kv_bytes_per_token
 
-    def decode_step(self, st, n=None):
-        """One decode step of the first n sessions of the batch (all by default)."""
+    def decode_step(self, st):
+        """One decode step of the batch: the step's token appended, then attention, in one launch."""
         B, g, dec = self.B, self.g, self.dec
-        n = dec.b.batch if n is None else n
-        B.ag_kv_append(self.cache, dec.k_new[:n], dec.v_new[:n], dec.bt[:n], dec.prefix[:n], dec.new[:n], dec.cu[:n + 1],
-                       n, stream=st)
-        B.ag_attn_decode(self.cache, dec.q[:n], dec.out[:n], dec.bt[:n], dec.ctx[:n], self.max_ctx, g.num_q_heads, g.scale,
-                         self.ws, stream=st)
+        B.ag_decode_step(self.cache, dec.k_new, dec.v_new, dec.q, dec.out, dec.bt, dec.ctx, self.max_ctx, g.num_q_heads,
+                         g.scale, self.ws, stream=st)
 
     def prefill_loop(self, st):
         B, g, cold, res, cache = self.B, self.g, self.cold, self.res, self.cache
@@ -382,16 +433,49 @@ def bench_mixed(args, torch, B, I, info):
             r["prefill_loops"] = loops[0]
         return r
 
+    def check_decode_while_prefill_runs(dstream, pstream):
+        """The decode output of a step taken while the prefill loop runs on the other partition, against the
+        oracle (every row)."""
+        from oracle import oracle as O       # check leg
+        m, g = load.m, load.g
+        kp, vp = I.zero_pool(g.pool_shape, g.dtype), I.zero_pool(g.pool_shape, g.dtype)
+        for b in (m.decode_fill, m.decode):
+            O.kv_append(kp, vp, g.dtype, b.k_new, b.v_new, b.block_tables, b.prefix_lens, b.new_lens, b.cu_new)
+        ref = O.decode(kp, vp, g.dtype, m.decode.q, m.decode.block_tables, m.decode.ctx_lens, g.num_q_heads, g.scale)
+        del kp, vp
+        ds, ps = torch.cuda.ExternalStream(dstream), torch.cuda.ExternalStream(pstream)
+        load.dec.out.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for _ in range(3):                   # about 8 ms of prefill work queued on the other partition
+            prefill_loop(pstream)
+        for _ in range(4):                   # the steps run beside it; the last one's output is checked
+            decode_step(dstream)
+        ds.synchronize()
+        busy = not ps.query()                # the prefill stream still had work when the last step finished
+        got = I.stored_to_f64(load.dec.out.view(torch.int16).cpu().numpy().view(np.uint16), g.dtype)
+        ps.synchronize()
+        err = np.abs(got - ref)
+        return {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+                "rel_fro": float(np.linalg.norm(got - ref) / np.linalg.norm(ref)), "rows": int(ref.shape[0]),
+                "prefill_stream_busy_when_the_step_finished": bool(busy)}
+
     old_si = sys.getswitchinterval()
     sys.setswitchinterval(1e-5)
     out = {"decode_kv_bytes_per_step": kv_bytes, "prefill_tokens_per_loop": prefill_tokens,
-           "prefill_flops_per_loop": prefill_flops, "splits": {}}
+           "prefill_flops_per_loop": prefill_flops, "decode_entry_point": "ag_decode_step",
+           "p99_ratio_baseline": "decode alone on the same CU partition, prefill stream idle (isolates interference)",
+           "p99_ratio_vs_full_gpu_baseline": "decode alone on the whole GPU (adds what the partition itself costs)",
+           "splits": {}}
     try:
-        out["decode_alone_full_gpu"] = run(None, None, args.mixed_steps)
+        full = out["decode_alone_full_gpu"] = run(None, None, args.mixed_steps)
         plain_a = B.ag_stream_create_cumask([0xFFFFFFFF] * ((total_cus + 31) // 32))
         plain_b = B.ag_stream_create_cumask([0xFFFFFFFF] * ((total_cus + 31) // 32))
-        out["unmasked_two_streams"] = run(plain_a, plain_b, args.mixed_steps)
-        for cus in (32, 64, 96):
+        un = out["unmasked_two_streams"] = run(plain_a, plain_b, args.mixed_steps)
+        un["p99_ratio_vs_full_gpu"] = un["p99_us"] / full["p99_us"]
+        B.ag_stream_destroy(plain_a)
+        B.ag_stream_destroy(plain_b)
+        # the stated splits {32, 64, 96} and, beside them, larger decode shares
+        for cus in (32, 64, 96, 128, 160):
             k = cus // n_xcd
             sd = B.ag_stream_create_cumask(B.ag_cumask_build(total_cus, n_xcd, 0, k))
             sp = B.ag_stream_create_cumask(B.ag_cumask_build(total_cus, n_xcd, k, per - k))
@@ -399,17 +483,22 @@ def bench_mixed(args, torch, B, I, info):
             pp, pxp = placement(torch, B, sp)
             alone = run(sd, None, args.mixed_steps)
             mixed = run(sd, sp, args.mixed_steps)
-            out["splits"][str(cus)] = {
+            e = {
                 "decode_cus_seen": len(pd), "prefill_cus_seen": len(pp), "overlap": len(pd & pp),
                 "decode_cus_per_xcd": sorted(pxd.values()), "prefill_cus_per_xcd": sorted(pxp.values()),
                 "decode_alone": alone, "with_prefill": mixed,
                 "p99_ratio": mixed["p99_us"] / alone["p99_us"], "p50_ratio": mixed["p50_us"] / alone["p50_us"],
+                "p99_ratio_vs_full_gpu": mixed["p99_us"] / full["p99_us"],
+                "p50_ratio_vs_full_gpu": mixed["p50_us"] / full["p50_us"],
+                "within_1p5x_of_same_partition_alone": bool(mixed["p99_us"] <= 1.5 * alone["p99_us"]),
+                "within_1p5x_of_full_gpu_alone": bool(mixed["p99_us"] <= 1.5 * full["p99_us"]),
             }
-            log("mixed", cus, json.dumps(out["splits"][str(cus)]))
+            if cus == 64 and not args.no_cpu_baseline:
+                e["check_vs_oracle"] = check_decode_while_prefill_runs(sd, sp)
+            out["splits"][str(cus)] = e
+            log("mixed", cus, json.dumps(e))
             B.ag_stream_destroy(sd)
             B.ag_stream_destroy(sp)
-        B.ag_stream_destroy(plain_a)
-        B.ag_stream_destroy(plain_b)
     finally:
         sys.setswitchinterval(old_si)
     log("mixed", json.dumps({k: v for k, v in out.items() if k != "splits"}))
@@ -457,12 +546,18 @@ def bench_merged(args, torch, B, I):
     ctx = c.chunk.ctx_lens.astype(np.int64)
     kv_bytes = int(ctx.sum()) * g.kv_bytes_per_token
     qo_bytes = 2 * ch.total * g.num_q_heads * g.head_dim * 2
+    bt_bytes = int(((ctx + g.page_size - 1) // g.page_size).sum()) * 4
     out = {
         "sessions_decoding": nd, "sessions_resuming": int(len(ctx) - nd), "rows": ch.total,
         "resume_rows": [int(x) for x in c.chunk.new_lens[nd:]],
         "merged_us": t_m * 1e6, "decode_then_resume_us": t_s * 1e6, "resume_entry_point_on_all_us": t_r * 1e6,
         "merged_split_kernel_us": prof["mean_us"],
         "kv_bytes_once": kv_bytes, "merged_GBps_of_kv_once": (kv_bytes + qo_bytes) / t_m / 1e9,
+        # algorithmic bytes: the K/V of every session once + Q + O + 4 B per referenced page
+        "roofline": roofline("hbm", (kv_bytes + qo_bytes + bt_bytes) / (prof["mean_us"] * 1e-6) / 1e9, HBM_PEAK_GBPS, "GB/s",
+                             "merged_split_kernel.decode_queue", kernel="merged_split_kernel", kernel_us=prof["mean_us"],
+                             algorithmic_bytes=kv_bytes + qo_bytes + bt_bytes,
+                             whole_call_frac=(kv_bytes + qo_bytes + bt_bytes) / t_m / 1e9 / HBM_PEAK_GBPS),
         "flops": c.chunk.attn_flops(),
         "max_abs_merged_vs_separate": float((out_m.float() - out_s.float()).abs().max()),
         "max_abs_merged_vs_resume_all": float((out_m.float() - out_r.float()).abs().max()),
@@ -757,8 +852,7 @@ def main():
     ap.add_argument("--workloads", default="decode,cold,resume,mixed")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=4, help="disjoint session sets the decode step rotates over")
-    ap.add_argument("--mixed-steps", type=int, default=1000)
-    ap.add_argument("--graph", action="store_true", help="decode workload: also time the step replayed from a HIP graph")
+    ap.add_argument("--mixed-steps", type=int, default=2000)
     ap.add_argument("--merged-rows", default="16,64", help="range of the resume chunks' rows in the merged workload")
     ap.add_argument("--ctl-interval-ms", type=float, default=20.0, help="control interval of the closed-loop workload")
     ap.add_argument("--ctl-intervals", type=int, default=100)
@@ -808,10 +902,8 @@ def main():
     if d:
         line.update({
             "value": d["step_GBps"], "ms_per_step": d["ms_per_step"],
-            "roofline": {"bound": "hbm", "achieved": d["kernel_GBps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                         "frac": d["kernel_GBps"] / HBM_PEAK_GBPS,
-                         "traffic": measured_traffic("decode_split_kernel.config2"),
-                         "kernel": d["kernel"], "kernel_us": d["kernel_us"], "algorithmic_bytes": d["attn_bytes"]},
+            "roofline": roofline("hbm", d["kernel_GBps"], HBM_PEAK_GBPS, "GB/s", "ag_attn_decode.config2",
+                                 kernel=d["kernel"], kernel_us=d["kernel_us"], algorithmic_bytes=d["attn_bytes"]),
             "cpu_baseline": d.get("cpu_baseline"),
         })
     else:

@@ -178,6 +178,35 @@ AG_API ag_status ag_attn_decode_static(const ag_kv_cache* cache, const void* q, 
                                 int32_t num_q_heads, float scale, void* stream);
 
 /*
+ * One decode step in one launch (paper Sec. III-B: every active stream produces one token per decode step;
+ * Sec. II-A: the step first extends the cache by that token, then attends over it): for every session s the
+ * step's token - row s of k_new / v_new, [B][Hkv][D] - is written to logical position ctx_lens[s] - 1 exactly as
+ * ag_kv_append would write it, and the query of row s attends to all ctx_lens[s] positions exactly as
+ * ag_attn_decode would: pools and output are bit-identical to those two calls one after the other.  What
+ * differs is the schedule: the workgroup whose share of the batch ends a (session, KV head) context appends
+ * its token before reading that page, and the workgroup that is last to finish a context's segments (an
+ * atomic count per context) merges them, always in segment order.  ctx_lens[s] = 0: nothing is appended for s
+ * and its output row is zeros.  Sessions must not share the page a token is appended to (as for ag_kv_append).
+ * Supported shapes: bf16, head_dim 128, page_size 16, Hq / Hkv <= 16 (AG_ERR_UNSUPPORTED otherwise: use the two
+ * calls).  k_new, v_new, q and the pools 16-byte aligned.
+ * Workspace: at least ag_decode_step_workspace_bytes() bytes, 16-byte aligned.  Its first
+ * AG_DECODE_STEP_COUNTER_BYTES bytes are the counters (one per session and KV head: batch * Hkv may not exceed
+ * AG_DECODE_STEP_COUNTER_BYTES / 4, AG_ERR_INVALID_ARG otherwise): they must be ZERO before the first call
+ * that uses the workspace (zero-fill it once after allocating it); every call leaves them zero, so later calls
+ * - of any batch, head count or context bound the workspace is large enough for - need no clearing.  The rest
+ * may hold anything.  Calls sharing a workspace must be ordered on one stream.  A call that does not run to
+ * its end (device reset) leaves the counters undefined: clear them again.
+ */
+#define AG_DECODE_STEP_COUNTER_BYTES (256u << 10)
+AG_API size_t    ag_decode_step_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t max_ctx);
+AG_API ag_status ag_decode_step(const ag_kv_cache* cache, const void* k_new, const void* v_new,   /* device [B][Hkv][D] */
+                         const void* q, void* out,                               /* device [B][Hq][D] */
+                         const int32_t* block_tables, int32_t max_pages_per_seq,
+                         const int32_t* ctx_lens,                                /* device [B] */
+                         int32_t batch, int32_t max_ctx, int32_t num_q_heads, float scale,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * The decode queue's batch in one launch (paper Sec. III-A: short resume prefills are merged with decodes;
  * Algorithm 1: a request joins Q_D if it is a decode or no longer than B_prefill).  Semantics are exactly
  * ag_attn_resume's: session s brings new_lens[s] >= 0 query rows at positions prefix_lens[s] + i that attend
@@ -250,9 +279,10 @@ AG_API ag_status ag_debug_validate(const ag_kv_cache* cache, const int32_t* bloc
 
 /*
  * Measurement aid, not part of the serving path.  While enabled on the calling
- * host thread, every launch of the main kernel of an attention call (the
- * split kernel of ag_attn_decode, the tile kernel of ag_attn_prefill /
- * ag_attn_resume, or the general kernel) is bracketed by a pair of HIP events
+ * host thread, every attention call's main kernel work (both kernels of
+ * ag_attn_decode, split and merge; the one kernel of ag_decode_step; the tile
+ * kernel of ag_attn_prefill / ag_attn_resume; the split kernel of
+ * ag_attn_merged; or the general kernel) is bracketed by a pair of HIP events
  * recorded on the launch stream, up to max_launches pairs.  ag_prof_collect
  * waits for the recorded events, returns the mean / min / max duration of
  * those launches in microseconds (any out-pointer may be NULL) and starts a

@@ -21,7 +21,7 @@ AG_F32, AG_BF16 = 0, 1
 
 EXPORTS = [
     "ag_kv_append", "ag_attn_prefill", "ag_attn_resume", "ag_attn_decode_workspace_bytes", "ag_attn_decode",
-    "ag_attn_decode_static",
+    "ag_attn_decode_static", "ag_decode_step_workspace_bytes", "ag_decode_step",
     "ag_attn_merged_workspace_bytes", "ag_attn_merged",
     "ag_stream_create_cumask", "ag_stream_destroy", "ag_cumask_build", "ag_probe_placement", "ag_device_info",
     "ag_debug_validate", "ag_prof_enable", "ag_prof_collect", "ag_prof_disable", "ag_status_string",
@@ -92,6 +92,9 @@ def lib():
     l.ag_attn_decode_workspace_bytes.restype = C.c_size_t
     l.ag_attn_decode.argtypes = [cp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp, C.c_size_t, vp]
     l.ag_attn_decode_static.argtypes = [cp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp]
+    l.ag_decode_step_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    l.ag_decode_step_workspace_bytes.restype = C.c_size_t
+    l.ag_decode_step.argtypes = [cp, vp, vp, vp, vp, i32p, i32, i32p, i32, i32, i32, C.c_float, vp, C.c_size_t, vp]
     l.ag_attn_merged_workspace_bytes.argtypes = [i32, i32, i32]
     l.ag_attn_merged_workspace_bytes.restype = C.c_size_t
     l.ag_attn_merged.argtypes = [cp, vp, vp, i32p, i32, i32p, i32p, i32p, i32, i32, i32, i32, i32, C.c_float, vp,
@@ -134,7 +137,7 @@ def lib():
     l.ag_pager_page_state.argtypes = [vp, i32]
     l.ag_pager_get_stats.argtypes = [vp, C.POINTER(ag_pager_stats)]
     for name in EXPORTS:
-        if name not in ("ag_attn_decode_workspace_bytes", "ag_attn_merged_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
+        if name not in ("ag_attn_decode_workspace_bytes", "ag_decode_step_workspace_bytes", "ag_attn_merged_workspace_bytes", "ag_status_string", "ag_last_error", "ag_version"):
             getattr(l, name).restype = C.c_int
     l.ag_status_string.argtypes = [C.c_int]
     for name in ("ag_status_string", "ag_last_error", "ag_version"):
@@ -257,6 +260,22 @@ def ag_attn_decode_static(cache: KVCache, q, out, block_tables, ctx_lens, max_ct
     _check(lib().ag_attn_decode_static(C.byref(c), _ptr(q), _ptr(out), _i32(block_tables), block_tables.shape[1],
                                        _i32(ctx_lens), ctx_lens.shape[0], max_ctx, num_q_heads, scale,
                                        _stream(stream)))
+
+
+AG_DECODE_STEP_COUNTER_BYTES = 256 << 10
+
+
+def ag_decode_step_workspace_bytes(batch: int, num_q_heads: int, head_dim: int, max_ctx: int) -> int:
+    return int(lib().ag_decode_step_workspace_bytes(batch, num_q_heads, head_dim, max_ctx))
+
+
+def ag_decode_step(cache: KVCache, k_new, v_new, q, out, block_tables, ctx_lens, max_ctx: int, num_q_heads: int,
+                   scale: float, workspace: torch.Tensor, stream=None):
+    """`workspace` must have been zero-filled once before its first use (every call leaves its counters zero)."""
+    c = cache.c_struct()
+    _check(lib().ag_decode_step(C.byref(c), _ptr(k_new), _ptr(v_new), _ptr(q), _ptr(out), _i32(block_tables),
+                                block_tables.shape[1], _i32(ctx_lens), ctx_lens.shape[0], max_ctx, num_q_heads, scale,
+                                _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def ag_attn_merged_workspace_bytes(total_new: int, num_q_heads: int, max_ctx: int) -> int:

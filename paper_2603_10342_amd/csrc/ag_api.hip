@@ -278,6 +278,52 @@ ag_status ag_attn_decode_static(const ag_kv_cache* cache, const void* q, void* o
                          nullptr, 0, true, stream);
 }
 
+size_t ag_decode_step_workspace_bytes(int32_t batch, int32_t num_q_heads, int32_t head_dim, int32_t max_ctx)
+{
+    if (batch <= 0 || num_q_heads <= 0 || head_dim <= 0 || max_ctx < 0) return 0;
+    return decode_step_workspace_bytes(batch, num_q_heads, head_dim, max_ctx);
+}
+
+ag_status ag_decode_step(const ag_kv_cache* cache, const void* k_new, const void* v_new, const void* q, void* out,
+                         const int32_t* block_tables, int32_t max_pages_per_seq, const int32_t* ctx_lens, int32_t batch,
+                         int32_t max_ctx, int32_t num_q_heads, float scale, void* workspace, size_t workspace_bytes,
+                         void* stream)
+{
+    CacheView c;
+    ag_status st = view_cache(cache, &c);
+    if (st) return st;
+    if (!k_new || !v_new || !q || !out || !block_tables || !ctx_lens) { set_error("a required pointer is NULL"); return AG_ERR_INVALID_ARG; }
+    if (batch <= 0 || max_pages_per_seq <= 0 || max_ctx < 0) {
+        set_error("batch=%d max_pages_per_seq=%d max_ctx=%d: sizes must be positive", batch, max_pages_per_seq, max_ctx);
+        return AG_ERR_INVALID_ARG;
+    }
+    if ((st = check_heads(c, num_q_heads)) || (st = check_scale(scale))) return st;
+    if ((int64_t)max_ctx > (int64_t)max_pages_per_seq * c.ps) {
+        set_error("max_ctx %d exceeds max_pages_per_seq * page_size = %lld", max_ctx, (long long)max_pages_per_seq * c.ps);
+        return AG_ERR_INVALID_ARG;
+    }
+    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)c.k | (uintptr_t)c.v) % 16) {
+        set_error("k_new, v_new and the pools must be 16-byte aligned");
+        return AG_ERR_INVALID_ARG;
+    }
+    AttnArgs a;
+    a.q = q; a.out = out; a.c = c; a.bt = block_tables; a.max_pages = max_pages_per_seq;
+    a.prefix_lens = nullptr; a.new_lens = nullptr; a.cu_new = nullptr; a.ctx_lens = ctx_lens;
+    a.batch = batch; a.total_rows = batch; a.max_new = 1; a.max_ctx = max_ctx; a.hq = num_q_heads; a.scale = scale;
+    if (!decode_mfma_supported(a)) {
+        set_error("ag_decode_step covers bf16, head_dim 128, page_size 16, at most 16 query heads per KV head, 16-byte "
+                  "aligned q; use ag_kv_append + ag_attn_decode for other shapes");
+        return AG_ERR_UNSUPPORTED;
+    }
+    const size_t need = decode_step_workspace_bytes(batch, num_q_heads, c.d, max_ctx);
+    if (workspace_bytes < need || !workspace) {
+        set_error("decode-step workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+        return AG_ERR_WORKSPACE;
+    }
+    if (((uintptr_t)workspace) % 16) { set_error("decode-step workspace must be 16-byte aligned"); return AG_ERR_INVALID_ARG; }
+    return launch_decode_step(a, k_new, v_new, workspace, (hipStream_t)stream);
+}
+
 ag_status ag_stream_create_cumask(void** stream_out, const uint32_t* cu_mask_words, int32_t n_words)
 {
     if (!stream_out || !cu_mask_words || n_words <= 0 || n_words > 64) {

@@ -65,6 +65,9 @@ ag_status launch_prefill_mfma(const AttnArgs& a, hipStream_t st);
 bool      decode_mfma_supported(const AttnArgs& a);
 size_t    decode_workspace_bytes(int batch, int hq, int d, int max_ctx);
 ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st);
+// the whole decode step (append + attention + merge) in one launch; same shapes as the matrix-core decode
+size_t    decode_step_workspace_bytes(int batch, int hq, int d, int max_ctx);
+ag_status launch_decode_step(const AttnArgs& a, const void* k_new, const void* v_new, void* ws, hipStream_t st);
 // Address, on the current device, of the library's own decode workspace (AG_DECODE_STATIC_SCRATCH_BYTES bytes);
 // looked up once per device, allocates nothing.
 ag_status decode_static_scratch(void** ptr_out);

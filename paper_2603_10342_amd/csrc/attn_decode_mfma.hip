@@ -62,9 +62,24 @@ inline int pieces_max(int max_ctx) { return (((max_ctx + 31) / 32) - 1) / kMinSt
 // Workspace: header [q, then the exclusive step count before each session], partials O, partials (m, l).
 inline size_t header_ints(int batch) { return ((size_t)batch + 1 + 3) & ~(size_t)3; }
 
+// What the whole-step form of the kernel gets on top: the step's new token of every session (one row each),
+// which it appends itself, and one counter per (session, KV head), zero on entry and zero again on exit.
+struct StepArgs {
+    const __bf16* k_new;        // [B][Hkv][D]
+    const __bf16* v_new;
+    int32_t* counters;          // [B * Hkv]
+};
+
+// kStep = false: the split half of ag_attn_decode (partials to the workspace, merged by decode_merge_kernel).
+// kStep = true: the whole decode step in one launch (ag_decode_step).  The workgroup whose share holds the last
+// step of a (session, KV head) pair first writes the step's token into the pair's last page - the wave that will
+// read that page does it, and waits for its own stores before it loads the page - and the workgroup that is
+// last to finish a pair's segments (an atomic count per pair) merges them, in segment order whoever comes last,
+// so the result does not depend on timing; a pair that lies inside one share is normalised and written directly.
+template <bool kStep>
 __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_t* __restrict__ hdr,
                                                               float* __restrict__ ws_o, float* __restrict__ ws_ml,
-                                                              int pmax)
+                                                              int pmax, StepArgs sa)
 {
     __shared__ float s_o[4][16][D];     // per wave, per (padded) head: unnormalised O
     __shared__ float s_m[4][16];
@@ -73,6 +88,7 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
     constexpr int kQRow = 2 * D + 16;
     __shared__ __attribute__((aligned(16))) unsigned char s_q[16 * kQRow];
     __shared__ int s_start[3];          // session holding the workgroup's first step, steps before it, its length
+    __shared__ int s_arrived;           // kStep: how many of the pair's segments had been finished before this one
 
     const int B = a.batch, hkv = a.c.hkv, hq = a.hq;
     const int G = hq / hkv;
@@ -92,11 +108,16 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
         total = s_red[0] + s_red[1] + s_red[2] + s_red[3];
         __syncthreads();
     }
+    if (kStep) {                        // a session without context gets a row of zeros (no workgroup's share holds it)
+        for (int se = wg; se < B; se += W)
+            if (a.ctx_lens[se] <= 0)
+                for (int idx = tid; idx < hq * D; idx += 256) ((__bf16*)a.out)[(int64_t)se * hq * D + idx] = (__bf16)0.0f;
+    }
     const int F = hkv * total;
     if (F == 0) return;
     const int q = max(kMinSteps, (F + W - 1) / W);
     const int f0 = wg * q;              // q <= kMaxSteps by the launcher's choice of W: no overflow
-    if (wg == 0 && tid == 0) hdr[0] = q;
+    if (!kStep && wg == 0 && tid == 0) hdr[0] = q;
     if (f0 >= F) return;                // uniform over the workgroup
     const int f1 = min(f0 + q, F);
     {
@@ -118,10 +139,10 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
             const int chunk = s_red[0] + s_red[1] + s_red[2] + s_red[3];
             const int excl = carry + woff + incl - n;
             if (n > 0 && hkv * excl <= f0 && f0 < hkv * (excl + n)) { s_start[0] = s; s_start[1] = excl; s_start[2] = len; }
-            if (wg == 0 && s < B) hdr[1 + s] = excl;       // workgroup 0 publishes the plan for the merge kernel
+            if (!kStep && wg == 0 && s < B) hdr[1 + s] = excl;       // workgroup 0 publishes the plan for the merge kernel
             __syncthreads();
             carry += chunk;
-            if (wg != 0 && hkv * carry > f0) break;         // found (uniform); workgroup 0 goes on publishing
+            if ((kStep || wg != 0) && hkv * carry > f0) break;     // found (uniform); workgroup 0 goes on publishing
         }
     }
     int s = s_start[0];
@@ -159,21 +180,40 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
 
         // Q of the pair's G heads goes through LDS (rows of 256 B + 16 B of padding, zero beyond G): as the B
         // operand, column = head r, k = channels kk*32 + c*8 .. +7, read when a step needs it rather than
-        // held in 16 registers across the loads
-        {
-            int tid_q = tid;                                 // 256 threads: 16 heads x 16 pieces of 16 bytes
-            asm volatile("" : "+v"(tid_q));
-            const int head = tid_q >> 4, ch = tid_q & 15;
-            u32x4 x = {0, 0, 0, 0};
-            if (head < G)
-                x = *reinterpret_cast<const u32x4*>((const __bf16*)a.q + ((int64_t)s * hq + (int64_t)g * G + head) * D + ch * 8);
-            *reinterpret_cast<u32x4*>(s_q + head * kQRow + ch * 16) = x;
-        }
+        // held in 16 registers across the loads.
+        // kStep: the segment that ends the pair also appends the step's token (position ctx - 1).  The wave whose
+        // quarter holds the pair's last step writes it - 16 lanes a 16-byte piece of the key each, every lane two
+        // channels of the value - and waits for these stores before it loads that step (below).
+        // Every load of this prologue (Q, page ids, the new token) is issued before the first of them is used.
+        const bool appends = kStep && u + k == n && w == (k - 1) / per;        // uniform over the wave
+        int tid_q = tid;                                     // 256 threads: 16 heads x 16 pieces of 16 bytes
+        asm volatile("" : "+v"(tid_q));
+        const int head_q = tid_q >> 4, ch_q = tid_q & 15;
+        u32x4 qx = {0, 0, 0, 0};
+        if (head_q < G)
+            qx = *reinterpret_cast<const u32x4*>((const __bf16*)a.q + ((int64_t)s * hq + (int64_t)g * G + head_q) * D + ch_q * 8);
         // physical pages of this wave's steps (lane i: page i of its run, clamped to the session's last page)
+        const int last_lp = ((ctx + PS - 1) >> 4) - 1;
         int my_pid = 0;
-        if (my_n > 0) {
-            const int lp = min(2 * my_u + lane_s, ((ctx + PS - 1) >> 4) - 1);
-            my_pid = a.bt[(int64_t)s * a.max_pages + lp];
+        if (my_n > 0) my_pid = a.bt[(int64_t)s * a.max_pages + min(2 * my_u + lane_s, last_lp)];
+        u32x4 new_k = {0, 0, 0, 0};
+        __bf16 new_v0 = (__bf16)0.0f, new_v1 = (__bf16)0.0f;
+        if (appends) {
+            const __bf16* ks = sa.k_new + ((int64_t)s * hkv + g) * D;
+            const __bf16* vs = sa.v_new + ((int64_t)s * hkv + g) * D;
+            if (lane_s < 16) new_k = *reinterpret_cast<const u32x4*>(ks + lane_s * 8);
+            new_v0 = vs[lane_s];
+            new_v1 = vs[lane_s + 64];
+        }
+        *reinterpret_cast<u32x4*>(s_q + head_q * kQRow + ch_q * 16) = qx;
+        if (appends) {
+            const int slot = (ctx - 1) & (PS - 1);
+            const int64_t page = __builtin_amdgcn_readlane(my_pid, last_lp - 2 * my_u);   // the run holds the last page
+            __bf16* kdst = (__bf16*)a.c.k + (page * hkv + g) * (int64_t)(D * PS);
+            __bf16* vdst = (__bf16*)a.c.v + (page * hkv + g) * (int64_t)(D * PS);
+            if (lane_s < 16) *reinterpret_cast<u32x4*>(kdst + (lane_s * PS + slot) * 8) = new_k;
+            vdst[v_offset(slot, lane_s, PS, D)] = new_v0;
+            vdst[v_offset(slot, lane_s + 64, PS, D)] = new_v1;
         }
 
         float m = -INFINITY, lsum = 0.0f;
@@ -186,6 +226,10 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
 #pragma unroll 1
         for (int st = 0; st < my_n; ++st) {
             StepRegs x;
+            if (appends && st == my_n - 1) {             // the token this wave appended lies in the page loaded next
+                __builtin_amdgcn_s_waitcnt(0x0070 | (0xF << 8));          // vmcnt(0): its stores have been performed
+                asm volatile("" ::: "memory");
+            }
             {
                 const int64_t pA = __builtin_amdgcn_readlane(my_pid, 2 * st);
                 const int64_t pB = __builtin_amdgcn_readlane(my_pid, 2 * st + 1);
@@ -257,7 +301,10 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
         __syncthreads();
 
         // the pair starts at flat step base + g n; its segments are numbered from the workgroup holding that step
-        const int piece = wg - (base + g * n) / q;
+        const int first_wg = (base + g * n) / q;
+        const int piece = wg - first_wg;
+        const int pieces = (base + g * n + n - 1) / q - first_wg + 1;
+        const bool direct = kStep && pieces == 1;        // the pair lies inside this share: no partial, no merge
         if (piece < pmax) {
             for (int idx = tid_e; idx < G * D; idx += 256) {
                 const int head = idx >> 7, d = idx & (D - 1);
@@ -271,9 +318,37 @@ __global__ __launch_bounds__(256, 4) void decode_split_kernel(AttnArgs a, int32_
                     acc += fw * s_o[ww][head][d];
                     l += fw * s_l[ww][head];
                 }
-                const int64_t slot = ((int64_t)s * hq + (int64_t)g * G + head) * pmax + piece;
-                ws_o[slot * D + d] = acc;
-                if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = l; }
+                const int64_t row = (int64_t)s * hq + (int64_t)g * G + head;
+                if (direct) {
+                    ((__bf16*)a.out)[row * D + d] = (__bf16)(acc / l);
+                } else {
+                    const int64_t slot = row * pmax + piece;
+                    if (kStep) {                       // read by another workgroup of this launch: device-scope stores
+                        store_coherent(ws_o + slot * D + d, acc);
+                        if (d == 0) { store_coherent(ws_ml + slot * 2, ms); store_coherent(ws_ml + slot * 2 + 1, l); }
+                    } else {
+                        ws_o[slot * D + d] = acc;
+                        if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = l; }
+                    }
+                }
+            }
+        }
+        if (kStep && !direct) {
+            // Count this segment in; whoever completes the pair merges all its segments, in their order.  The
+            // partials were stored at device scope (they go past this XCD's caches), the barrier below waits
+            // until every thread's stores have been performed before the count is raised, and the merging
+            // workgroup reads them at device scope after it has seen the full count: no cache-wide write-back
+            // or invalidate is needed (a device-wide fence costs a multiple of the whole step here).
+            __syncthreads();
+            if (tid_e == 0) s_arrived = __hip_atomic_fetch_add(&sa.counters[s * hkv + g], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (s_arrived == pieces - 1) {
+                for (int idx = tid_e; idx < G * D; idx += 256) {
+                    const int head = idx >> 7, d = idx & (D - 1);
+                    const int64_t row = (int64_t)s * hq + (int64_t)g * G + head;
+                    ((__bf16*)a.out)[row * D + d] = (__bf16)merge_partials<true>(ws_o, ws_ml, row * pmax, min(pieces, pmax), d);
+                }
+                if (tid_e == 0) sa.counters[s * hkv + g] = 0;      // as the next call expects it
             }
         }
         __syncthreads();                                 // s_o is rewritten by the next segment
@@ -398,14 +473,49 @@ ag_status launch_decode_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     if (f_max > (1 << 30)) { set_error("decode batch of %lld steps of 32 tokens is beyond one launch", (long long)f_max); return AG_ERR_INVALID_ARG; }
     if (a.max_ctx > 0) {
         const int grid = workgroups_for(f_max, st);
+        // the event bracket covers both kernels of the call: the merge kernel writes the output the byte count includes
         prof_before(st);
-        hipLaunchKernelGGL(decode_split_kernel, dim3(grid), dim3(256), 0, st, a, hdr, ws_o, ws_ml, pmax);
-        prof_after(st);
+        hipLaunchKernelGGL(decode_split_kernel<false>, dim3(grid), dim3(256), 0, st, a, hdr, ws_o, ws_ml, pmax, StepArgs{});
         ag_status e = hip_check(hipGetLastError(), "decode split launch");
         if (e) return e;
     }
     hipLaunchKernelGGL(decode_merge_kernel, dim3(a.batch * a.hq), dim3(128), 0, st, a, hdr, ws_o, ws_ml, pmax);
+    prof_after(st);
     return hip_check(hipGetLastError(), "decode merge launch");
+}
+
+// ---- the whole step in one launch ----
+// Workspace: a counter region of fixed size at the start - wherever the partials of a call of another shape
+// may have landed, they never land here, so the counters stay zero from call to call - then the split
+// kernel's workspace.
+static size_t step_counter_bytes(int, int) { return AG_DECODE_STEP_COUNTER_BYTES; }
+
+size_t decode_step_workspace_bytes(int batch, int hq, int d, int max_ctx)
+{
+    if (batch <= 0) return 0;
+    return step_counter_bytes(batch, hq) + decode_workspace_bytes(batch, hq, d, max_ctx);
+}
+
+ag_status launch_decode_step(const AttnArgs& a, const void* k_new, const void* v_new, void* ws, hipStream_t st)
+{
+    if ((int64_t)a.batch * a.c.hkv * (int64_t)sizeof(int32_t) > (int64_t)AG_DECODE_STEP_COUNTER_BYTES) {
+        set_error("batch * num_kv_heads = %lld exceeds the %d counters of a decode-step workspace", (long long)a.batch * a.c.hkv,
+                  (int)(AG_DECODE_STEP_COUNTER_BYTES / sizeof(int32_t)));
+        return AG_ERR_INVALID_ARG;
+    }
+    const int pmax = pieces_max(a.max_ctx);
+    int32_t* counters = (int32_t*)ws;
+    int32_t* hdr = (int32_t*)((unsigned char*)ws + step_counter_bytes(a.batch, a.hq));
+    float* ws_o = (float*)(hdr + header_ints(a.batch));
+    float* ws_ml = ws_o + (size_t)a.batch * a.hq * pmax * D;
+    const int64_t f_max = (int64_t)a.c.hkv * a.batch * ((a.max_ctx + 31) / 32);
+    if (f_max > (1 << 30)) { set_error("decode batch of %lld steps of 32 tokens is beyond one launch", (long long)f_max); return AG_ERR_INVALID_ARG; }
+    const int grid = workgroups_for(std::max<int64_t>(f_max, 1), st);
+    prof_before(st);
+    hipLaunchKernelGGL(decode_split_kernel<true>, dim3(grid), dim3(256), 0, st, a, hdr, ws_o, ws_ml, pmax,
+                       StepArgs{(const __bf16*)k_new, (const __bf16*)v_new, counters});
+    prof_after(st);
+    return hip_check(hipGetLastError(), "decode step launch");
 }
 
 }  // namespace ag

@@ -52,6 +52,12 @@ struct StepRegs {       // one wave's K and V operands for 32 tokens (two pages)
 // The partials (m, l, O[D]) of one (row, head) lie at slots base .. base + n - 1 (n >= 1, the first of them with a
 // finite m); combine them in slot order - reproducible - four at a time, so that a group's loads are in flight
 // together instead of one dependent round trip per partial.  Returns channel d of the normalised output.
+// kCoherent: the partials were written by other workgroups of the SAME launch (device-scope stores, see
+// store_coherent): read them with device-scope loads, which do not hit in this XCD's caches.
+__device__ __forceinline__ float load_coherent(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void store_coherent(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+template <bool kCoherent = false>
 __device__ __forceinline__ float merge_partials(const float* __restrict__ ws_o, const float* __restrict__ ws_ml,
                                                 int64_t base, int n, int d)
 {
@@ -61,9 +67,9 @@ __device__ __forceinline__ float merge_partials(const float* __restrict__ ws_o, 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int64_t p = base + min(i0 + j, n - 1);
-            mi[j] = ws_ml[p * 2];
-            li[j] = ws_ml[p * 2 + 1];
-            oi[j] = ws_o[p * D + d];
+            mi[j] = kCoherent ? load_coherent(ws_ml + p * 2) : ws_ml[p * 2];
+            li[j] = kCoherent ? load_coherent(ws_ml + p * 2 + 1) : ws_ml[p * 2 + 1];
+            oi[j] = kCoherent ? load_coherent(ws_o + p * D + d) : ws_o[p * D + d];
             if (i0 + j >= n) mi[j] = -INFINITY;
         }
         const float m_new = fmaxf(fmaxf(ms, fmaxf(mi[0], mi[1])), fmaxf(mi[2], mi[3]));

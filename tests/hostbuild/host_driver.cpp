@@ -39,6 +39,8 @@ bool decode_mfma_supported(const AttnArgs& a) { return a.c.dtype == AG_BF16 && a
 size_t decode_workspace_bytes(int batch, int hq, int d, int max_ctx) { return (size_t)batch * hq * (size_t)(d + 2) * 4 * (size_t)(max_ctx / 256 + 2); }
 ag_status launch_decode_mfma(const AttnArgs&, void* ws, hipStream_t) { CHECK(ws != nullptr); ++g_launches[L_DECODE]; return AG_OK; }
 ag_status decode_static_scratch(void** p) { *p = g_fake_scratch; return AG_OK; }
+size_t decode_step_workspace_bytes(int batch, int hq, int d, int max_ctx) { return 256 + decode_workspace_bytes(batch, hq, d, max_ctx); }
+ag_status launch_decode_step(const AttnArgs&, const void* k, const void* v, void* ws, hipStream_t) { CHECK(k && v && ws); ++g_launches[L_DECODE]; return AG_OK; }
 bool merged_mfma_supported(const AttnArgs& a) { return decode_mfma_supported(a); }
 size_t merged_workspace_bytes(int rows, int hq, int max_ctx) { return (size_t)rows * hq * 520 * (size_t)(max_ctx / 256 + 2); }
 ag_status launch_merged_mfma(const AttnArgs&, void*, hipStream_t) { ++g_launches[L_MERGED]; return AG_OK; }
@@ -78,6 +80,12 @@ static void test_validation()
     CHECK(ag_attn_decode_static(&c, q.data(), out.data(), bt.data(), 8, lens.data(), 4, 128, 8, 0.1f, nullptr) == AG_OK);
     CHECK(ag_attn_decode_static(&c, q.data(), out.data(), bt.data(), 1 << 20, lens.data(), 4096, 1 << 24, 8, 0.1f, nullptr) == AG_ERR_WORKSPACE);
     CHECK(ag::g_launches[ag::L_DECODE] == 2);
+    std::vector<float> wss(ag_decode_step_workspace_bytes(4, 8, 128, 128) / 4);
+    CHECK(ag_decode_step(&c, q.data(), q.data(), q.data(), out.data(), bt.data(), 8, lens.data(), 4, 128, 8, 0.1f, wss.data(), wss.size() * 4, nullptr) == AG_OK);
+    CHECK(ag_decode_step(&c, q.data(), nullptr, q.data(), out.data(), bt.data(), 8, lens.data(), 4, 128, 8, 0.1f, wss.data(), wss.size() * 4, nullptr) == AG_ERR_INVALID_ARG);
+    CHECK(ag_decode_step(&c, q.data(), q.data(), q.data(), out.data(), bt.data(), 8, lens.data(), 4, 128, 8, 0.1f, wss.data(), wss.size() * 4 - 16, nullptr) == AG_ERR_WORKSPACE);
+    CHECK(ag_decode_step(&f, q.data(), q.data(), q.data(), out.data(), bt.data(), 8, lens.data(), 4, 128, 8, 0.1f, wss.data(), wss.size() * 4, nullptr) == AG_ERR_UNSUPPORTED);
+    CHECK(ag::g_launches[ag::L_DECODE] == 3);
     std::vector<float> wsm(ag_attn_merged_workspace_bytes(64, 8, 128) / 4);
     CHECK(ag_attn_merged(&c, q.data(), out.data(), bt.data(), 8, lens.data(), lens.data(), cu.data(), 4, 64, 16, 128, 8, 0.1f,
                          wsm.data(), wsm.size() * 4, nullptr) == AG_OK);
