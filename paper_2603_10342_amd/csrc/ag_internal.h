@@ -79,4 +79,9 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st);
 
 ag_status launch_probe(uint32_t* ids_out, int n_wg, int spin_cycles, hipStream_t st);
 
+// CUs of the current device, and the CUs the stream's launches may use (the bits of its CU mask; all of them
+// for a stream without one).  Launchers that size a grid to the partition use these.
+int device_cus();
+int stream_cus(hipStream_t st);
+
 }  // namespace ag

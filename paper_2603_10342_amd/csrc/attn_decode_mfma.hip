@@ -386,6 +386,8 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(AttnArgs a, const int
     out[d] = (__bf16)merge_partials(ws_o, ws_ml, (int64_t)row * pmax, pieces, d);
 }
 
+}  // namespace
+
 // CUs of the current device.
 int device_cus()
 {
@@ -415,6 +417,8 @@ int stream_cus(hipStream_t st)
     for (uint32_t i = 0; i < n_words; ++i) n += __builtin_popcount(words[i]);
     return n > 0 && n <= all ? n : all;
 }
+
+namespace {
 
 // Workgroups of a launch: the shares are equal, so what matters is that every CU gets the same number of
 // them, and as few as the longest share (kMaxSteps) allows: each workgroup pays the plan and each segment a
