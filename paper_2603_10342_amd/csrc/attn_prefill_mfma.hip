@@ -219,6 +219,26 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
                 pre[k] = in && a.prefix_lens ? a.prefix_lens[ss] : 0;
                 cu[k] = in ? a.cu_new[ss] : 0;
             }
+            // A batch that fits one pass is walked longest context first: workgroups start in list order, and a
+            // launch ends sooner when the tiles left for its end are the short ones (each has P + position keys
+            // to go through).  Every wave ranks the sessions itself; equal contexts keep the given order.
+            int sess = ln;                          // the session this lane's entry describes
+            if (a.batch <= 64) {
+                const int key = ln < a.batch ? pre[0] + lens[0] : -1;
+                const int key0 = __builtin_amdgcn_readlane(key, 0);
+                if (__builtin_amdgcn_ballot_w64(ln < a.batch && key != key0) != 0) {       // uniform
+                    int rank = 0;                   // sessions ahead of this one: longer, or as long and earlier
+                    for (int o = 0; o < a.batch; ++o) {
+                        const int ko = __builtin_amdgcn_readlane(key, o);
+                        rank += (ko > key || (ko == key && o < ln)) ? 1 : 0;
+                    }
+                    if (ln >= a.batch) rank = ln;   // entries without a session stay where they are
+                    sess = __builtin_amdgcn_ds_permute(rank << 2, sess);
+                    lens[0] = __builtin_amdgcn_ds_permute(rank << 2, lens[0]);
+                    pre[0] = __builtin_amdgcn_ds_permute(rank << 2, pre[0]);
+                    cu[0] = __builtin_amdgcn_ds_permute(rank << 2, cu[0]);
+                }
+            }
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
                 if (s >= 0) break;                  // uniform
@@ -234,7 +254,7 @@ __global__ __launch_bounds__(64 * NW, kWavesPerSimd) void prefill_mfma_kernel(At
                 if (j < before + pass_total) {      // uniform
                     const unsigned long long hit = __builtin_amdgcn_ballot_w64(j < before + incl);
                     const int l = __builtin_ctzll(hit);              // first session whose tiles reach past j
-                    s = s0 + 64 * k + l;
+                    s = s0 + 64 * k + (k == 0 ? __builtin_amdgcn_readlane(sess, l) : l);
                     N = __builtin_amdgcn_readlane(len, l);
                     P = __builtin_amdgcn_readlane(pre[k], l);
                     row0 = __builtin_amdgcn_readlane(cu[k], l);
