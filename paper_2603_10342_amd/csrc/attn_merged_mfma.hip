@@ -38,6 +38,10 @@ using namespace splitk;
 
 enum { kKeysItem = 0, kRowsItem = 1 };
 
+#ifndef AG_MERGED_STAGES
+#define AG_MERGED_STAGES 3
+#endif
+
 // plan[0] = number of items; item i is plan[4 + 4i ..]: session, first row (within the session's chunk), rows, kind.
 // row_ctx[row] = keys the item that holds query row `row` was cut over: prefix + rows of the chunk up to the
 // item's last (what the merge kernel needs to count the row's partials, without walking plan -> session -> prefix).
@@ -89,6 +93,9 @@ __global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restr
     }
     if (threadIdx.x == 0) plan[0] = min(carry, total_rows);
 }
+
+// A lane's 8 weights under the reference maximum may sum to this much before the ordered path takes over.
+constexpr float kWeightSumLimit = 16384.0f;
 
 constexpr int kSmemBytes = 4 * 16 * D * 4 + 2 * 4 * 16 * 4;     // 33280: partials of four waves, or two K/V stages
 
@@ -273,7 +280,11 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
 // [half][channel][8 keys]).  Wave w copies block w of the stage: four 1 KiB wave-wide loads.
 constexpr int kKPage = 4096 + 128;
 constexpr int kStage = 2 * kKPage + 2 * 4096;       // 16640
-static_assert(2 * kStage <= kSmemBytes, "two stages must fit the shared buffer");
+// Steps in LDS at a time: one being read, the others in flight.  With one step in flight a rows item advances by
+// one step per memory round trip (2 us and more under load, for a third of a microsecond of arithmetic).
+constexpr int kStages = AG_MERGED_STAGES;
+static_assert(kStages >= 2 && kStages <= 4, "the waits below count at most two later requests");
+constexpr int smem_bytes(bool rows) { return rows ? (kStages * kStage > kSmemBytes ? kStages * kStage : kSmemBytes) : kSmemBytes; }
 
 template <int kSteps, int R>
 __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
@@ -294,7 +305,7 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     // this wave's rows: groups j = 0..R-1 are rows wrow0 + j * tq + (0..tq-1) of the item
     const int wrow0 = w * R * tq;
     const bool wave_on = wrow0 < nt;                          // uniform over the wave
-    const int pos_hi = P + t0 + min(nt, wrow0 + R * tq) - 1;  // last key any row of this wave may see
+    const int pos_lo = P + t0 + wrow0;                        // last key every column of this wave may see
     const int col_row = r / G, col_head = r - col_row * G;
     int pos[R];
     bf16x8 qf[R][4];
@@ -323,7 +334,7 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     auto request = [&](int st) {
         const int64_t pid = __builtin_amdgcn_readlane(my_pid, 2 * st + (wu & 1));
         const unsigned char* src = pool + (pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 16;
-        const unsigned dst = lds_address(smem) + (unsigned)(st & 1) * kStage + blk_off;
+        const unsigned dst = lds_address(smem) + (unsigned)(st % kStages) * kStage + blk_off;
 #pragma unroll
         for (int i = 0; i < 4; ++i) load_to_lds(src + i * 1024, dst + i * 1024);
     };
@@ -345,31 +356,87 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     const int k_lane = (r >> 3) * kKPage + (c * PS + (r & 7)) * 16;           // + kk * 1024; + 128 for slots 8..15
     const int v_lane = 2 * kKPage + (c >> 1) * 4096 + ((c & 1) * D + r) * 16;   // + mb * 256
 
-    request(0);
+    // The page ids are needed for the first request anyway; waiting here for every ordinary load (Q among them)
+    // also tells the compiler's wait-count pass that nothing it knows of is pending: it does not see the direct
+    // loads, and would otherwise put a full wait in front of each later request to be safe about my_pid.
+    AG_WAIT_VMCNT(0);
+#pragma unroll
+    for (int i = 0; i < kStages - 1; ++i)
+        if (i < n_steps) request(i);
+
+    // what every wave does at the top of step st, rows or not: its block of the step has landed (all but the
+    // requests made after it, four loads each), so has everybody's, and all waves are done with step st - 1,
+    // whose stage the next request overwrites
+    auto advance = [&](int st) {
+        const int later = min(kStages - 2, n_steps - 1 - st);
+        if (later >= 2) AG_WAIT_VMCNT(8); else if (later == 1) AG_WAIT_VMCNT(4); else AG_WAIT_VMCNT(0);
+        __syncthreads();
+        if (st + kStages - 1 < n_steps) request(st + kStages - 1);
+    };
+
+    if (!wave_on) {                                  // a wave without rows only moves its share of the bytes
+#pragma unroll 1
+        for (int st = 0; st < n_steps; ++st) advance(st);
+        return;
+    }
+
+    // A step whose keys lie above all of this wave's rows (only the last step can: an item has at most 32 rows)
+    // goes through the same code with every weight masked to zero: an exit inside the loop would make the
+    // compiler copy all of O in every step to join the two paths.
 #pragma unroll 1
     for (int st = 0; st < n_steps; ++st) {
-        AG_WAIT_VMCNT(0);                            // this wave's block of step st has landed
-        __syncthreads();                             // ... and everybody's; all waves are done with step st - 1
-        if (st + 1 < n_steps) request(st + 1);       // into the stage step st - 1 was read from
+        advance(st);
         const int tok0 = start + st * 32;
-        if (wave_on && tok0 <= pos_hi) {
-            const unsigned char* stage = smem + (st & 1) * kStage;
-            const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
-            f32x4 s1[R], s2[R];
+        const unsigned char* stage = smem + (st % kStages) * kStage;
+        const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
+        // all K operands of the step are requested from LDS before the first product, and all V operands
+        // before the softmax arithmetic, which hides their latency
+        bf16x8 k1[4], k2[4];
 #pragma unroll
-            for (int j = 0; j < R; ++j) { s1[j] = f32x4{0.f, 0.f, 0.f, 0.f}; s2[j] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        for (int kk = 0; kk < 4; ++kk) {
+            k1[kk] = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024);
+            k2[kk] = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024 + 128);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        f32x4 s1[R], s2[R];
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                const bf16x8 k1 = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024);
-                const bf16x8 k2 = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024 + 128);
+        for (int j = 0; j < R; ++j) { s1[j] = f32x4{0.f, 0.f, 0.f, 0.f}; s2[j] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    s1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[j][kk], s1[j], 0, 0, 0);
-                    s2[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2, qf[j][kk], s2[j], 0, 0, 0);
-                }
+        for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+            for (int j = 0; j < R; ++j) {
+                s1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[kk], qf[j][kk], s1[j], 0, 0, 0);
+                s2[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2[kk], qf[j][kk], s2[j], 0, 0, 0);
             }
-            bf16x8 pb[R];
-            float alpha[R];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+
+        // Common case: the weights under the reference maximum each column already has (any common shift
+        // cancels in O / l, so m need not be the exact running maximum), and a check afterwards that no
+        // lane's sum of 8 weights exceeds 2^14 - so no weight does; inf and NaN (a column that has seen no
+        // key yet has m = -inf) fail it too.  No maximum, no rescaling of O.  Keys above the wave's first row
+        // need the visibility test; below it every key is visible to every column.
+        bf16x8 pb[R];
+        float psum[R];
+        const bool diag = tok0 + 31 > pos_lo;       // uniform over the wave
+        bool redo = false;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            const int keep = diag ? pos[j] + 1 - tokb : 16;
+            float ps = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[j][i], sl2, -m[j]));
+                float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[j][i], sl2, -m[j]));
+                if (diag) { p1 = (i < keep) ? p1 : 0.f; p2 = (8 + i < keep) ? p2 : 0.f; }
+                ps += p1 + p2;
+                pb[j][i] = (__bf16)p1;
+                pb[j][4 + i] = (__bf16)p2;
+            }
+            psum[j] = ps;
+            redo |= !(ps <= kWeightSumLimit);
+        }
+        if (__builtin_amdgcn_ballot_w64(redo) != 0) {     // uniform over the wave: the ordered path
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const int keep = pos[j] + 1 - tokb;  // key tokb + i is visible to this column iff i < keep
@@ -384,46 +451,51 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
                 mx = fmaxf(mx, __shfl_xor(mx, 32));
                 const float m_new = fmaxf(m[j], mx);
                 const float m_ref = m_new == -INFINITY ? 0.f : m_new;       // see keys_item
-                alpha[j] = __builtin_amdgcn_exp2f(m[j] - m_ref);
-                float psum = 0.f;
+                const float alpha = __builtin_amdgcn_exp2f(m[j] - m_ref);
+                float ps = 0.f;
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
-                    psum += p;
+                    ps += p;
                     pb[j][e] = (__bf16)p;
                 }
-                lsum[j] = lsum[j] * alpha[j] + psum;
+                lsum[j] = lsum[j] * alpha + ps;
                 m[j] = m_new;
+#pragma unroll
+                for (int mb = 0; mb < 8; ++mb) o[j][mb] *= alpha;
             }
-            const bool tail = tok0 + 32 > ctx_all;   // slots past the session's last token may hold anything
+        } else {
+#pragma unroll
+            for (int j = 0; j < R; ++j) lsum[j] += psum[j];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 v[8];
+#pragma unroll
+        for (int mb = 0; mb < 8; ++mb) v[mb] = *reinterpret_cast<const bf16x8*>(stage + v_lane + mb * 256);
+        if (tok0 + 32 > ctx_all) {                   // slots past the session's last token may hold anything
             const int keep_v = ctx_all - tokb;
 #pragma unroll
-            for (int mb = 0; mb < 8; ++mb) {
-                bf16x8 v = *reinterpret_cast<const bf16x8*>(stage + v_lane + mb * 256);
-                if (tail) v = keep_quads(v, keep_v, keep_v - 8);
+            for (int mb = 0; mb < 8; ++mb) v[mb] = keep_quads(v[mb], keep_v, keep_v - 8);
+        }
 #pragma unroll
-                for (int j = 0; j < R; ++j) {
-                    o[j][mb] *= alpha[j];
-                    o[j][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v, pb[j], o[j][mb], 0, 0, 0);
-                }
-            }
+        for (int mb = 0; mb < 8; ++mb) {
+#pragma unroll
+            for (int j = 0; j < R; ++j) o[j][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[mb], pb[j], o[j][mb], 0, 0, 0);
         }
     }
 
     // every wave holds the whole part for its rows: partials go straight to the workspace
-    if (wave_on) {
 #pragma unroll
-        for (int j = 0; j < R; ++j) {
-            const int row = wrow0 + j * tq + col_row;
-            float l = lsum[j];
-            l += __shfl_xor(l, 16);
-            l += __shfl_xor(l, 32);
-            if (col_row < tq && row < nt) {
-                const int64_t slot = (((int64_t)a.cu_new[s] + t0 + row) * hq + (int64_t)g * G + col_head) * n_splits_max + split;
+    for (int j = 0; j < R; ++j) {
+        const int row = wrow0 + j * tq + col_row;
+        float l = lsum[j];
+        l += __shfl_xor(l, 16);
+        l += __shfl_xor(l, 32);
+        if (col_row < tq && row < nt) {
+            const int64_t slot = (((int64_t)a.cu_new[s] + t0 + row) * hq + (int64_t)g * G + col_head) * n_splits_max + split;
 #pragma unroll
-                for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(ws_o + slot * D + mb * 16 + c * 4) = o[j][mb];
-                if (c == 0) { ws_ml[slot * 2] = m[j]; ws_ml[slot * 2 + 1] = l; }
-            }
+            for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(ws_o + slot * D + mb * 16 + c * 4) = o[j][mb];
+            if (c == 0) { ws_ml[slot * 2] = m[j]; ws_ml[slot * 2 + 1] = l; }
         }
     }
 }
@@ -435,7 +507,7 @@ __global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnA
                                                                            const int32_t* __restrict__ plan,
                                                                            int n_splits_max, int tq)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemBytes];
+    __shared__ __attribute__((aligned(16))) unsigned char smem[smem_bytes(kRows)];
     const int item = blockIdx.z;
     if (item >= plan[0]) return;
     const int32_t* e = plan + 4 + 4 * item;
