@@ -26,8 +26,10 @@
 // multiple of splits * KV heads, itself a multiple of 8 at 8 KV heads), so what they fetch again comes from
 // that XCD's L2.
 #include <algorithm>
+#include <atomic>
 
 #include "attn_split_common.h"
+#include "attn_tile32.h"
 #include "lds_dma.h"
 
 namespace ag {
@@ -37,10 +39,6 @@ namespace {
 using namespace splitk;
 
 enum { kKeysItem = 0, kRowsItem = 1 };
-
-#ifndef AG_MERGED_STAGES
-#define AG_MERGED_STAGES 3
-#endif
 
 // plan[0] = number of items; item i is plan[4 + 4i ..]: session, first row (within the session's chunk), rows, kind.
 // row_ctx[row] = keys the item that holds query row `row` was cut over: prefix + rows of the chunk up to the
@@ -274,229 +272,178 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
     }
 }
 
-// ---- rows item: four waves x R groups of rows over the same keys, K / V steps staged in LDS -------------------
-// LDS stage: K page A, K page B (each 4 KiB as stored, [chunk][slot][8 channels]; page B sits 128 bytes further
-// than a multiple of 256 so that the two pages' rows fall on different banks), V page A, V page B (4 KiB each,
-// [half][channel][8 keys]).  Wave w copies block w of the stage: four 1 KiB wave-wide loads.
-constexpr int kKPage = 4096 + 128;
-constexpr int kStage = 2 * kKPage + 2 * 4096;       // 16640
-// Steps in LDS at a time: one being read, the others in flight.  With one step in flight a rows item advances by
-// one step per memory round trip (2 us and more under load, for a third of a microsecond of arithmetic).
-constexpr int kStages = AG_MERGED_STAGES;
-static_assert(kStages >= 2 && kStages <= 4, "the waits below count at most two later requests");
-constexpr int smem_bytes(bool rows) { return rows ? (kStages * kStage > kSmemBytes ? kStages * kStage : kSmemBytes) : kSmemBytes; }
+// ---- rows item: four waves x 32 columns over the same keys, in the prefill kernel's 64-key tiles ---------------
+// Wave w holds column groups 2w and 2w + 1 of the item (group j = tokens j * tq .. + tq - 1, column r of a group =
+// token r / G, head r % G): 32 columns, the B operand of the 32x32x16 products.  The part's keys are walked in
+// tiles of 64 (four pages) that the workgroup brings into LDS by direct global-to-LDS loads - three K stages,
+// two V stages, tile layouts and software pipeline as in the prefill kernel (attn_tile32.h) - and every wave
+// writes the partial (m, l, O) of its columns for the part straight to the workspace.
+constexpr int kRowsLds = (tile32::kKStages + 2) * tile32::kTile;        // 80 KiB
 
-template <int kSteps, int R>
+template <int kSteps>
 __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
-                                          int n_splits_max, int tq, const ItemCtx& it, unsigned char* smem)
+                                          int n_splits_max, int tq, const ItemCtx& it, unsigned char* lds)
 {
-    static_assert(kSteps <= 8, "a part of a rows item spans at most 64 pages (one page id per lane)");
-    const int s = it.s, t0 = it.t0, nt = it.nt, split = it.split, g = it.g;
-    const int P = it.P, ctx_all = it.ctx_all, ctx = it.ctx, start = it.start;
-    const int end = min(ctx, start + it.part);
-    const int n_steps = (end - start + 31) >> 5;             // >= 1, uniform over the workgroup
+    using tile32::BN;
+    using tile32::kKStages;
+    using tile32::kTile;
+    constexpr int kPer = 4;                 // direct loads per wave for a K tile, and for a V tile
+    const int s = it.s, g = it.g, P = it.P, t0 = it.t0, nt = it.nt;
+    const int hkv = a.c.hkv, hq = a.hq, G = hq / hkv;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+    const int wu = __builtin_amdgcn_readfirstlane(w);           // the same value, known to be uniform
+    const int n = lane & 31, hi = lane >> 5;
 
-    const int hkv = a.c.hkv, hq = a.hq;
-    const int G = hq / hkv;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int wu = __builtin_amdgcn_readfirstlane(w);        // the same value, known to be uniform
-    const int r = lane & 15, c = lane >> 4;
+    // key tiles of the part: absolute tiles tb .. tb + n_tiles - 1 (parts start at multiples of 128 keys)
+    const int end = min(it.ctx, it.start + it.part);
+    const int tb = it.start / BN;
+    const int n_tiles = (end - 1) / BN + 1 - tb;                 // >= 1
 
-    // this wave's rows: groups j = 0..R-1 are rows wrow0 + j * tq + (0..tq-1) of the item
-    const int wrow0 = w * R * tq;
-    const bool wave_on = wrow0 < nt;                          // uniform over the wave
-    const int pos_lo = P + t0 + wrow0;                        // last key every column of this wave may see
+    // this lane's column; columns without a row carry the item's last row (their results are not stored)
+    const int r = n & 15;
     const int col_row = r / G, col_head = r - col_row * G;
-    int pos[R];
-    bf16x8 qf[R][4];
+    const int token = (2 * w + (n >> 4)) * tq + col_row;
+    const bool on = col_row < tq && token < nt;
+    const int row = on ? token : nt - 1;
+    const int qpos = P + t0 + row;                               // logical position of this lane's query
+    const int w_first = 2 * w * tq;                              // the wave's first token
+    const int w_last = min(nt, w_first + 2 * tq) - 1;            // ... and last
+    // tiles of the part this wave uses (none if it has no rows, or if the part lies above all of them), and the
+    // first tile holding a key its first row may not see
+    const int wave_tiles = w_first < nt ? max(0, min(n_tiles, (P + t0 + w_last) / BN + 1 - tb)) : 0;
+    const int first_masked = (P + t0 + w_first + 1) / BN - tb;
+
+    const __bf16* kpool = (const __bf16*)a.c.k;
+    const __bf16* vpool = (const __bf16*)a.c.v;
+    // the block table is read-only for the kernel's lifetime: through the constant address space the (uniform)
+    // page-id loads are scalar loads
+    typedef const __attribute__((address_space(4))) int32_t* cptr_t;
+    const cptr_t bt = (cptr_t)(uintptr_t)(a.bt + (int64_t)s * a.max_pages);
+    const int last_page = (it.ctx_all - 1) >> 4;
+
+    // Q^T as B operand: column n, k-step ks covers channels ks * 16 + hi * 8 .. + 7
+    bf16x8 qf[8];
+    {
+        const __bf16* qp = (const __bf16*)a.q + (((int64_t)a.cu_new[s] + t0 + row) * hq + (int64_t)g * G + col_head) * D + hi * 8;
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int row = wrow0 + j * tq + col_row;
-        const bool on = col_row < tq && row < nt;
-        pos[j] = P + t0 + (on ? row : nt - 1);
-        const int64_t q_row = (int64_t)a.cu_new[s] + t0 + (on ? row : 0);
-        const __bf16* qrow = (const __bf16*)a.q + (q_row * hq + (int64_t)g * G + col_head) * D + c * 8;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            bf16x8 x = ld16(qrow + kk * 32);
-            if (!on) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            qf[j][kk] = x;
-        }
+        for (int ks = 0; ks < 8; ++ks) qf[ks] = ld16(qp + ks * 16);
     }
 
-    // physical pages of the part, one per lane (clamped to the last page the item's rows may see)
-    const int n_pages_ctx = (ctx + PS - 1) >> 4;
-    const int my_pid = a.bt[(int64_t)s * a.max_pages + min((start >> 4) + lane, n_pages_ctx - 1)];
-
-    // wave w brings in block w of a stage: K page A, K page B, V page A, V page B of the step
-    const unsigned char* const pool = (const unsigned char*)(wu < 2 ? a.c.k : a.c.v);
-    const unsigned blk_off = wu < 2 ? (unsigned)(wu & 1) * kKPage : 2u * kKPage + (unsigned)(wu & 1) * 4096u;
-    auto request = [&](int st) {
-        const int64_t pid = __builtin_amdgcn_readlane(my_pid, 2 * st + (wu & 1));
-        const unsigned char* src = pool + (pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 16;
-        const unsigned dst = lds_address(smem) + (unsigned)(st % kStages) * kStage + blk_off;
+    unsigned char* const k_lds = lds;                            // K tile t at k_lds + (t % 3) * kTile
+    unsigned char* const v_lds = lds + kKStages * kTile;         // V tile t at v_lds + (t % 2) * kTile
+    const int kpg = lane >> 4, kslot = lane & 15;                // K: lane = key of the tile (page, slot)
+    const int kmask[4] = {kpg == 0 ? -1 : 0, kpg == 1 ? -1 : 0, kpg == 2 ? -1 : 0, kpg == 3 ? -1 : 0};
+    struct Pages { int k; int v; };                              // this LANE's page of a K tile; the wave's page of a V tile
+    auto pages_of = [&](int tk, int tv, Pages& pg) {             // absolute tile numbers
+        int pid[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) load_to_lds(src + i * 1024, dst + i * 1024);
+        for (int i = 0; i < 4; ++i) pid[i] = bt[min(tk * 4 + i, last_page)];
+        pg.k = (pid[0] & kmask[0]) | (pid[1] & kmask[1]) | (pid[2] & kmask[2]) | (pid[3] & kmask[3]);
+        pg.v = bt[min(tv * 4 + wu, last_page)];
+    };
+    // K: instruction i of wave w moves chunk 4 w + i of all 64 keys (four 256-byte runs, one per page);
+    // V: wave w moves page w of the tile, whose [half][channel][8 keys] layout is the LDS layout (four 1 KiB runs)
+    auto request_k = [&](int t, int mine) {
+        const unsigned char* src = (const unsigned char*)kpool + ((int64_t)mine * hkv + g) * (int64_t)(D * PS * 2) + (wu * kPer) * 256 + kslot * 16;
+        const unsigned dst = lds_address(k_lds) + (t % kKStages) * kTile + (wu * kPer) * 1024;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) load_to_lds(src + i * 256, dst + i * 1024);
+    };
+    auto request_v = [&](int stage, int pid) {
+        const unsigned char* src = (const unsigned char*)vpool + ((int64_t)pid * hkv + g) * (int64_t)(D * PS * 2) + lane * 16;
+        const unsigned dst = lds_address(v_lds) + stage * kTile + (wu * kPer) * 1024;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) load_to_lds(src + i * 1024, dst + i * 1024);
+    };
+    // slots of the session's last page that hold no token may contain anything (NaN included) and would poison
+    // the value product even under a zero weight: once V(tv) has landed, zero them in LDS
+    auto scrub_v = [&](int stage, int tv) {
+        const int keep = it.ctx_all - (tv * BN + wu * PS);       // slots < keep of this wave's page hold tokens
+        if (keep < PS) {                                         // uniform over the wave
+#pragma unroll
+            for (int i = 0; i < kPer; ++i) {
+                const int half = i >> 1;                         // run i = 2 * half + (channels 64..127)
+                u32x4* p = reinterpret_cast<u32x4*>(v_lds + stage * kTile + (wu * kPer + i) * 1024 + lane * 16);
+                *p = tile32::keep_quads(*p, keep - half * 4, keep - 8 - half * 4);
+            }
+        }
     };
 
     const float sl2 = a.scale * kLog2e;
-    float m[R], lsum[R];
-    f32x4 o[R][8];
+    float m = -INFINITY, lsum = 0.f;
+    tile32::f32x16 o[4];
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        m[j] = -INFINITY;
-        lsum[j] = 0.0f;
+    for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-        for (int mb = 0; mb < 8; ++mb) o[j][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+        for (int i = 0; i < 16; ++i) o[mb][i] = 0.f;
+    const unsigned char* const k_lane = k_lds + n * 16 + hi * 1024;
+    const unsigned char* const v_lane = v_lds + n * 16 + hi * 2048;
 
-    // operand addresses inside a stage, the decode step's lane assignment: score row r is slot (r & 7) of page
-    // (r >> 3), lane group c holds channels kk * 32 + c * 8 .. + 7; value rows are channels mb * 16 + r for the
-    // 8 keys of chunk (c & 1) of page (c >> 1)
-    const int k_lane = (r >> 3) * kKPage + (c * PS + (r & 7)) * 16;           // + kk * 1024; + 128 for slots 8..15
-    const int v_lane = 2 * kKPage + (c >> 1) * 4096 + ((c & 1) * D + r) * 16;   // + mb * 256
-
-    // The page ids are needed for the first request anyway; waiting here for every ordinary load (Q among them)
-    // also tells the compiler's wait-count pass that nothing it knows of is pending: it does not see the direct
-    // loads, and would otherwise put a full wait in front of each later request to be safe about my_pid.
+    // prologue: K(0) and K(1) requested and landed; the wait also tells the compiler that Q has arrived (it does
+    // not see the direct loads and would otherwise wait for everything before each later use)
+    Pages pg;
+    pages_of(tb, tb, pg);
+    request_k(0, pg.k);
+    pages_of(tb + min(1, n_tiles - 1), tb, pg);
+    request_k(1, pg.k);
+    pages_of(tb + min(2, n_tiles - 1), tb, pg);                  // what iteration 0 requests: V(0) and K(2)
     AG_WAIT_VMCNT(0);
-#pragma unroll
-    for (int i = 0; i < kStages - 1; ++i)
-        if (i < n_steps) request(i);
+    __syncthreads();
+    tile32::f32x16 sc[2];
+    bf16x8 pa[4], pb[4];
 
-    // what every wave does at the top of step st, rows or not: its block of the step has landed (all but the
-    // requests made after it, four loads each), so has everybody's, and all waves are done with step st - 1,
-    // whose stage the next request overwrites
-    auto advance = [&](int st) {
-        const int later = min(kStages - 2, n_steps - 1 - st);
-        if (later >= 2) AG_WAIT_VMCNT(8); else if (later == 1) AG_WAIT_VMCNT(4); else AG_WAIT_VMCNT(0);
+    // Iteration t: S(t) from K(t); then P(t) side by side with O += V(t-1).P(t-1).  It starts by requesting V(t)
+    // and K(t+2) and ends when V(t) and K(t+1) have landed.  Requests past the last tile repeat it into a buffer
+    // nobody reads, so the loop has one shape; every wave runs all n_tiles + 1 iterations (the barriers are
+    // workgroup-wide) and skips the pieces it does not need.
+    auto iter = [&](int t, bf16x8 (&p_prev)[4], bf16x8 (&p_cur)[4]) {
+        const int tv = min(t, n_tiles - 1);
+        request_v(t & 1, pg.v);
+        request_k(t + 2, pg.k);
+        Pages nxt;
+        pages_of(tb + min(t + 3, n_tiles - 1), tb + min(t + 1, n_tiles - 1), nxt);
+        const bool do_sm = t < wave_tiles, do_pv = t >= 1 && t <= wave_tiles;
+        const unsigned char* kb = k_lane + (t % kKStages) * kTile;
+        const unsigned char* vb = v_lane + ((t + 1) & 1) * kTile;    // V(t-1)
+        if (do_sm) {
+            tile32::qk_tile(kb, qf, sc);
+            if (t >= first_masked) {                 // the tile straddles this wave's diagonal
+                const int kbase = (tb + t) * BN + hi * 4;
+#pragma unroll
+                for (int b = 0; b < 2; ++b)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kbase + b * 32 + (i >> 2) * 8 + (i & 3);
+                        sc[b][i] = key <= qpos ? sc[b][i] : -INFINITY;
+                    }
+            }
+        }
+        tile32::softmax_and_value_product(do_sm, do_pv, vb, sc, sl2, m, lsum, p_prev, p_cur, o);
+        AG_WAIT_VMCNT(kPer);
+        scrub_v(t & 1, tb + tv);
+        pg = nxt;
         __syncthreads();
-        if (st + kStages - 1 < n_steps) request(st + kStages - 1);
     };
-
-    if (!wave_on) {                                  // a wave without rows only moves its share of the bytes
 #pragma unroll 1
-        for (int st = 0; st < n_steps; ++st) advance(st);
-        return;
+    for (int t = 0; t <= n_tiles; t += 2) {
+        iter(t, pb, pa);
+        if (t + 1 <= n_tiles) iter(t + 1, pa, pb);
     }
+    AG_WAIT_VMCNT(0);                                // the last (redundant) tile requests still write to LDS
 
-    // A step whose keys lie above all of this wave's rows (only the last step can: an item has at most 32 rows)
-    // goes through the same code with every weight masked to zero: an exit inside the loop would make the
-    // compiler copy all of O in every step to join the two paths.
-#pragma unroll 1
-    for (int st = 0; st < n_steps; ++st) {
-        advance(st);
-        const int tok0 = start + st * 32;
-        const unsigned char* stage = smem + (st % kStages) * kStage;
-        const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
-        // all K operands of the step are requested from LDS before the first product, and all V operands
-        // before the softmax arithmetic, which hides their latency
-        bf16x8 k1[4], k2[4];
+    // o[mb][q4 * 4 + e] is O^T[channel mb * 32 + q4 * 8 + hi * 4 + e][column n]; m is shared by the two lanes of a
+    // column, l is the sum of both
+    lsum += __shfl_xor(lsum, 32);
+    if (on) {
+        const int64_t slot = (((int64_t)a.cu_new[s] + t0 + token) * hq + (int64_t)g * G + col_head) * n_splits_max + it.split;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            k1[kk] = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024);
-            k2[kk] = *reinterpret_cast<const bf16x8*>(stage + k_lane + kk * 1024 + 128);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        f32x4 s1[R], s2[R];
+        for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
-        for (int j = 0; j < R; ++j) { s1[j] = f32x4{0.f, 0.f, 0.f, 0.f}; s2[j] = f32x4{0.f, 0.f, 0.f, 0.f}; }
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                s1[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1[kk], qf[j][kk], s1[j], 0, 0, 0);
-                s2[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k2[kk], qf[j][kk], s2[j], 0, 0, 0);
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const f32x4 x = {o[mb][q4 * 4], o[mb][q4 * 4 + 1], o[mb][q4 * 4 + 2], o[mb][q4 * 4 + 3]};
+                *reinterpret_cast<f32x4*>(ws_o + slot * D + mb * 32 + q4 * 8 + hi * 4) = x;
             }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
-        // Common case: the weights under the reference maximum each column already has (any common shift
-        // cancels in O / l, so m need not be the exact running maximum), and a check afterwards that no
-        // lane's sum of 8 weights exceeds 2^14 - so no weight does; inf and NaN (a column that has seen no
-        // key yet has m = -inf) fail it too.  No maximum, no rescaling of O.  Keys above the wave's first row
-        // need the visibility test; below it every key is visible to every column.
-        bf16x8 pb[R];
-        float psum[R];
-        const bool diag = tok0 + 31 > pos_lo;       // uniform over the wave
-        bool redo = false;
-#pragma unroll
-        for (int j = 0; j < R; ++j) {
-            const int keep = diag ? pos[j] + 1 - tokb : 16;
-            float ps = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(s1[j][i], sl2, -m[j]));
-                float p2 = __builtin_amdgcn_exp2f(__builtin_fmaf(s2[j][i], sl2, -m[j]));
-                if (diag) { p1 = (i < keep) ? p1 : 0.f; p2 = (8 + i < keep) ? p2 : 0.f; }
-                ps += p1 + p2;
-                pb[j][i] = (__bf16)p1;
-                pb[j][4 + i] = (__bf16)p2;
-            }
-            psum[j] = ps;
-            redo |= !(ps <= kWeightSumLimit);
-        }
-        if (__builtin_amdgcn_ballot_w64(redo) != 0) {     // uniform over the wave: the ordered path
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const int keep = pos[j] + 1 - tokb;  // key tokb + i is visible to this column iff i < keep
-                float xs[8];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    xs[i] = (i < keep) ? s1[j][i] * sl2 : -INFINITY;
-                    xs[4 + i] = (8 + i < keep) ? s2[j][i] * sl2 : -INFINITY;
-                }
-                float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m[j], mx);
-                const float m_ref = m_new == -INFINITY ? 0.f : m_new;       // see keys_item
-                const float alpha = __builtin_amdgcn_exp2f(m[j] - m_ref);
-                float ps = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
-                    ps += p;
-                    pb[j][e] = (__bf16)p;
-                }
-                lsum[j] = lsum[j] * alpha + ps;
-                m[j] = m_new;
-#pragma unroll
-                for (int mb = 0; mb < 8; ++mb) o[j][mb] *= alpha;
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < R; ++j) lsum[j] += psum[j];
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 v[8];
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb) v[mb] = *reinterpret_cast<const bf16x8*>(stage + v_lane + mb * 256);
-        if (tok0 + 32 > ctx_all) {                   // slots past the session's last token may hold anything
-            const int keep_v = ctx_all - tokb;
-#pragma unroll
-            for (int mb = 0; mb < 8; ++mb) v[mb] = keep_quads(v[mb], keep_v, keep_v - 8);
-        }
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb) {
-#pragma unroll
-            for (int j = 0; j < R; ++j) o[j][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v[mb], pb[j], o[j][mb], 0, 0, 0);
-        }
-    }
-
-    // every wave holds the whole part for its rows: partials go straight to the workspace
-#pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int row = wrow0 + j * tq + col_row;
-        float l = lsum[j];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        if (col_row < tq && row < nt) {
-            const int64_t slot = (((int64_t)a.cu_new[s] + t0 + row) * hq + (int64_t)g * G + col_head) * n_splits_max + split;
-#pragma unroll
-            for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(ws_o + slot * D + mb * 16 + c * 4) = o[j][mb];
-            if (c == 0) { ws_ml[slot * 2] = m[j]; ws_ml[slot * 2 + 1] = l; }
-        }
+        if (hi == 0) { ws_ml[slot * 2] = m; ws_ml[slot * 2 + 1] = lsum; }
     }
 }
 
@@ -507,7 +454,7 @@ __global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnA
                                                                            const int32_t* __restrict__ plan,
                                                                            int n_splits_max, int tq)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char smem[smem_bytes(kRows)];
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];     // kSmemBytes, or kRowsLds with rows items
     const int item = blockIdx.z;
     if (item >= plan[0]) return;
     const int32_t* e = plan + 4 + 4 * item;
@@ -528,7 +475,7 @@ __global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnA
     it.start = it.split * it.part;
     if (it.start >= it.ctx) return;                  // uniform over the workgroup
     if constexpr (kRows) {
-        if (kind == kRowsItem) { rows_item<kSteps, R>(a, ws_o, ws_ml, n_splits_max, tq, it, smem); return; }
+        if (kind == kRowsItem) { rows_item<kSteps>(a, ws_o, ws_ml, n_splits_max, tq, it, smem); return; }
     }
     keys_item<kSteps, R>(a, ws_o, ws_ml, n_splits_max, tq, it, smem);
 }
@@ -570,17 +517,35 @@ inline Layout layout(int total_rows, int hq, int max_ctx)
     return {(size_t)total_rows * hq * nsm * D, (size_t)total_rows * hq * nsm * 2, 4 + 4 * (size_t)total_rows, (size_t)total_rows};
 }
 
+template <int kSteps, int R, bool kRows>
+ag_status launch_one(dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml, const int32_t* plan, int nsm, int tq)
+{
+    constexpr int lds = kRows ? kRowsLds : kSmemBytes;
+    if constexpr (kRows) {                  // more dynamic LDS than a kernel may use without being told so
+        static std::atomic<bool> attr_set{false};
+        if (!attr_set.load()) {
+            ag_status e = hip_check(hipFuncSetAttribute((const void*)merged_split_kernel<kSteps, R, kRows>,
+                                                        hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+                                    "hipFuncSetAttribute(merged split)");
+            if (e) return e;
+            attr_set.store(true);
+        }
+    }
+    hipLaunchKernelGGL((merged_split_kernel<kSteps, R, kRows>), grid, dim3(256), lds, st, a, ws_o, ws_ml, plan, nsm, tq);
+    return AG_OK;
+}
+
 template <int R, bool kRows>
-void launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml,
-                  const int32_t* plan, int nsm, int tq)
+ag_status launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml,
+                       const int32_t* plan, int nsm, int tq)
 {
     switch (split) {
         case 2048:
-            if constexpr (!kRows) { hipLaunchKernelGGL((merged_split_kernel<16, R, false>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break; }
+            if constexpr (!kRows) return launch_one<16, R, false>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
             [[fallthrough]];     // not chosen for launches with rows items
-        case 1024: hipLaunchKernelGGL((merged_split_kernel<8, R, kRows>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        case 512:  hipLaunchKernelGGL((merged_split_kernel<4, R, kRows>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
-        default:   hipLaunchKernelGGL((merged_split_kernel<2, R, kRows>), grid, dim3(256), 0, st, a, ws_o, ws_ml, plan, nsm, tq); break;
+        case 1024: return launch_one<8, R, kRows>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+        case 512:  return launch_one<4, R, kRows>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+        default:   return launch_one<2, R, kRows>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
     }
 }
 
@@ -626,10 +591,11 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
     if (e) return e;
     const dim3 grid(nsm, a.c.hkv, (unsigned)items_max);
     prof_before(st);
-    if (R == 1) launch_split<1, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-    else if (!rows) launch_split<2, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-    else launch_split<2, true>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    if (R == 1) e = launch_split<1, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    else if (!rows) e = launch_split<2, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    else e = launch_split<2, true>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
     prof_after(st);
+    if (e) return e;
     if ((e = hip_check(hipGetLastError(), "merged split launch"))) return e;
     hipLaunchKernelGGL(merged_merge_kernel, dim3((unsigned)((int64_t)a.total_rows * a.hq)), dim3(128), 0, st, a, ws_o, ws_ml,
                        row_ctx, nsm, split);
