@@ -3,28 +3,31 @@
 // a request to Q_D when it is a decode or no longer than B_prefill).  bf16, head_dim 128, page 16.
 //
 // A session brings N >= 0 new query rows at positions P .. P + N - 1 (a decode is N = 1) that attend causally
-// to the session's keys: the semantics of the resume prefill.  The work is cut the way the decode step cuts
-// it - the keys a session's rows may see are split over workgroups, partial (m, l, O) per split, merged in
-// split order - because with few rows per session the launch is bound by reading K and V:
+// to the session's keys: the semantics of the resume prefill.  The keys a session's rows may see are cut over
+// workgroups, partial (m, l, O) per cut, merged in cut order, as in the decode step, because with few rows per
+// session the launch is bound by reading K and V.  A session's rows are cut into items of two kinds:
 //
-//   plan kernel     lists the items.  A group is tq = 16 / G consecutive rows of one session (G = query heads
-//                   per KV head): its tq x G (row, head) pairs fill the 16 columns of the matrix instruction
-//                   that the decode step leaves mostly empty.  Two kinds of item:
-//                     keys item  up to R groups; the four waves of a workgroup split the KEYS of the part, as in
-//                                the decode step, each K / V step loaded once into registers for the R groups;
-//                     rows item  up to 4 R groups (32 rows at G = 4, R = 2); the four waves split the ROWS and
-//                                all walk the same keys, which the workgroup brings into LDS once per step by
-//                                direct global-to-LDS loads (two stages), so a session's keys are fetched once
-//                                per 4 R groups instead of once per R.
-//                   Sessions with at most R groups of rows (decodes among them) become one keys item; longer
-//                   chunks become rows items plus, for a remainder of at most R groups, one keys item.
-//   split kernel    one workgroup per (item, KV head, split of the keys the item's last row may see), with a
-//                   visibility limit per column.
-//   merge kernel    one workgroup per (row, head) combines the splits in split order.
+//   keys item  up to R groups of rows (a group is tq = 16 / G consecutive rows, G = query heads per KV head: its
+//              tq x G (row, head) pairs fill the 16 columns of the matrix instruction that a decode leaves mostly
+//              empty).  Work on it streams: the four waves of a workgroup split the keys, each K / V step
+//              (32 keys) is loaded once into registers for the R groups - the decode step's loop with a
+//              visibility limit per column.  Bound by memory.
+//   rows item  up to 8 groups of rows (32 rows at G = 4): four waves x 32 columns walk the same keys in the
+//              prefill kernel's 64-key tiles, which the workgroup brings into LDS once (attn_tile32.h), so the
+//              keys are fetched once per 8 groups.  Bound by the matrix cores.
+//   A session has full rows items and a remainder that is a keys item if it has at most R groups of rows, else one
+//   more rows item; a decode, or any chunk of at most R groups, is one keys item.
 //
-// Items of one (session, KV head, split) are dealt to the same XCD (their linear workgroup ids differ by a
-// multiple of splits * KV heads, itself a multiple of 8 at 8 KV heads), so what they fetch again comes from
-// that XCD's L2.
+// The launch has exactly as many workgroups as the stream's CUs hold at once, and no planning launch: as in the
+// decode step, the work of each kind is laid end to end - the keys items' (session, KV head) pairs in steps of 32
+// keys, the rows items' (session, KV head, item) triples in tiles of 64 keys - and dealt in equal contiguous
+// shares, W_T workgroups sharing the tiles and the other W_K the steps.  Every workgroup derives the totals, the
+// two share sizes and its own starting point from the lengths on the device (a sum and a scan over the batch).
+// W_T : W_K follows the cost of a tile against a step, so that both kinds end together; the tile workgroups come
+// first in the grid, which spreads them over the CUs: a CU then holds matrix-bound and memory-bound work side by
+// side for the whole launch.  A share is one segment (part of one pair or triple) or the end of one and the
+// start of the next ones; each segment leaves a partial per (row, head), numbered by the workgroups the pair is
+// cut over, and the first workgroup publishes what the merge kernel needs to count them.
 #include <algorithm>
 #include <atomic>
 
@@ -38,88 +41,85 @@ namespace {
 
 using namespace splitk;
 
+#ifndef AG_MERGED_TILE_US
+#define AG_MERGED_TILE_US 2.15f
+#endif
+
+constexpr int kMinSteps = kMinSplit / 32;       // a streaming share is at least this many steps (256 keys)
+constexpr int kMinTiles = kMinSplit / 64;       // a tile share at least this many tiles (256 keys)
+constexpr int kSmemBytes = 4 * 16 * D * 4 + 2 * 4 * 16 * 4;             // 33280: partials of four waves
+constexpr int kRowsLds = (tile32::kKStages + 2) * tile32::kTile;        // 80 KiB: three K and two V tiles
+// What the split of the workgroups between the two kinds of work rests on (measured with timestamps inside the
+// kernel): a tile workgroup takes 2.1-2.2 us per 64-key tile; the streaming workgroups together move 369 steps of
+// 32 keys per microsecond on the whole device (6.0 TB/s) however many they are, as long as they are enough to
+// saturate the memory system; a single streaming workgroup cannot take a step in less than 0.57 us (what one CU
+// can draw, for its two workgroups).
+constexpr float kTileUs = AG_MERGED_TILE_US;
+constexpr float kDeviceStepsPerUs = 369.0f;
+constexpr float kStepUsAlone = 0.57f;
+
+__device__ __forceinline__ int steps_of(int ctx) { return ctx > 0 ? (ctx + 31) >> 5 : 0; }
+__device__ __forceinline__ int tiles_of(int ctx) { return ctx > 0 ? (ctx + 63) >> 6 : 0; }
+// Segments a pair of n units may be cut into when shares are at least `least` units.
+inline int pieces_max(int max_ctx) { return (((max_ctx + 31) / 32) - 1) / kMinSteps + 2; }
+
+// How a session's N rows are cut.  rk: rows of a full keys item; rw: rows of a full rows item, 0 if the launch
+// has no rows items (then no session brings more than rk rows).
+struct Cut {
+    int n_rows_items;       // rows item j holds rows [j rw, min(N, (j + 1) rw))
+    int k_t0, k_nt;         // rows of the keys item (none if k_nt = 0)
+};
+__device__ __forceinline__ Cut cut_of(int N, int rk, int rw)
+{
+    Cut c;
+    if (rw == 0) { c.n_rows_items = 0; c.k_t0 = 0; c.k_nt = max(N, 0); return c; }
+    const int full = N / rw, rem = N - full * rw;
+    c.n_rows_items = full + (rem > rk ? 1 : 0);
+    c.k_t0 = full * rw;
+    c.k_nt = rem > rk ? 0 : rem;
+    return c;
+}
+__device__ __forceinline__ int item_tiles(int N, int P, int rw, int j) { return tiles_of(P + min(N, (j + 1) * rw)); }
+__device__ __forceinline__ int session_steps(const Cut& c, int P) { return c.k_nt > 0 ? steps_of(P + c.k_t0 + c.k_nt) : 0; }
+__device__ __forceinline__ int session_tiles(const Cut& c, int N, int P, int rw)
+{
+    int t = 0;
+    for (int j = 0; j < c.n_rows_items; ++j) t += item_tiles(N, P, rw, j);
+    return t;
+}
+
+// What the merge kernel needs per query row: which kind of item holds it, the flat unit at which the item's
+// pair starts for KV head 0, the distance to the next head's pair, and the pair's length.
+struct RowInfo { int32_t kind, first, stride, n; };
 enum { kKeysItem = 0, kRowsItem = 1 };
 
-// plan[0] = number of items; item i is plan[4 + 4i ..]: session, first row (within the session's chunk), rows, kind.
-// row_ctx[row] = keys the item that holds query row `row` was cut over: prefix + rows of the chunk up to the
-// item's last (what the merge kernel needs to count the row's partials, without walking plan -> session -> prefix).
-// rk: rows of a full keys item; rw: rows of a full rows item, 0 if the launch has no rows items.
-__device__ __forceinline__ int items_of(int n, int rk, int rw)
-{
-    if (rw == 0) return (n + rk - 1) / rk;
-    return n / rw + (n % rw ? 1 : 0);
-}
-
-__global__ __launch_bounds__(256) void merged_plan_kernel(const int32_t* __restrict__ new_lens,
-                                                          const int32_t* __restrict__ prefix_lens,
-                                                          const int32_t* __restrict__ cu_new, int batch,
-                                                          int total_rows, int rk, int rw,
-                                                          int32_t* __restrict__ plan,
-                                                          int32_t* __restrict__ row_ctx)
-{
-    __shared__ int scan[256];
-    __shared__ int carry;
-    if (threadIdx.x == 0) carry = 0;
-    __syncthreads();
-    for (int base = 0; base < batch; base += 256) {
-        const int s = base + threadIdx.x;
-        const int n = s < batch ? new_lens[s] : 0;
-        const int P = (s < batch && prefix_lens) ? prefix_lens[s] : 0;
-        const int mine = items_of(n, rk, rw);
-        scan[threadIdx.x] = mine;
-        __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {   // inclusive scan
-            const int v = threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
-            __syncthreads();
-            scan[threadIdx.x] += v;
-            __syncthreads();
-        }
-        const int first = carry + scan[threadIdx.x] - mine;
-        const int step = rw ? rw : rk;
-        for (int i = 0; i < mine && first + i < total_rows; ++i) {     // (lengths that contradict the host's total
-            const int t0 = i * step;                                    //  never write past the plan)
-            const int nt = min(step, n - t0);
-            int32_t* e = plan + 4 + 4 * (first + i);
-            e[0] = s; e[1] = t0; e[2] = nt;
-            e[3] = (rw && nt > rk) ? kRowsItem : kKeysItem;
-            const int row0 = cu_new[s] + t0;
-            for (int x = 0; x < nt && row0 + x < total_rows; ++x) row_ctx[row0 + x] = P + t0 + nt;
-        }
-        __syncthreads();
-        if (threadIdx.x == 255) carry += scan[255];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) plan[0] = min(carry, total_rows);
-}
-
-// A lane's 8 weights under the reference maximum may sum to this much before the ordered path takes over.
-constexpr float kWeightSumLimit = 16384.0f;
-
-constexpr int kSmemBytes = 4 * 16 * D * 4 + 2 * 4 * 16 * 4;     // 33280: partials of four waves, or two K/V stages
-
-struct ItemCtx {        // what both kinds of item need; uniform over the workgroup
-    int s, t0, nt, split, g;
-    int P, ctx_all, ctx, start, part;
+// What a segment needs to know about its item; uniform over the workgroup.
+struct Seg {
+    int s, g;               // session, KV head
+    int t0, nt;             // the item's rows within the session's chunk
+    int P, ctx_all, ctx;    // prefix, prefix + chunk (slots below hold tokens), keys the item's last row may see
+    int u, k;               // the segment: units u .. u + k - 1 of the pair (steps of 32 keys, or tiles of 64)
+    int piece;              // which of the pair's partials this segment leaves
 };
 
-// ---- keys item: the decode step's loop with R column groups --------------------------------------------------
-template <int kSteps, int R>
-__device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
-                                          int n_splits_max, int tq, const ItemCtx& it, unsigned char* smem)
+// ---- a segment of a keys item: the decode step's loop with R column groups -----------------------------------
+template <int R>
+__device__ __forceinline__ void stream_segment(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
+                                               int pmax, int tq, const Seg& sg, unsigned char* smem)
 {
     float (*s_o)[16][D] = reinterpret_cast<float (*)[16][D]>(smem);                 // per wave, per column of one group
     float (*s_m)[16] = reinterpret_cast<float (*)[16]>(smem + 4 * 16 * D * 4);
     float (*s_l)[16] = s_m + 4;
 
-    const int s = it.s, t0 = it.t0, nt = it.nt, split = it.split, g = it.g;
-    const int P = it.P, ctx_all = it.ctx_all, ctx = it.ctx, start = it.start;
-    const int wave_tok = it.part >> 2;
-
+    const int s = sg.s, g = sg.g, t0 = sg.t0, nt = sg.nt, P = sg.P, ctx_all = sg.ctx_all, ctx = sg.ctx;
     const int hkv = a.c.hkv, hq = a.hq;
     const int G = hq / hkv;
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int r = lane & 15, c = lane >> 4;
-    const int wstart = start + w * wave_tok;
+    // the four waves take contiguous quarters of the segment's steps
+    const int per = (sg.k + 3) >> 2;
+    const int my_u = sg.u + w * per;
+    const int my_n = max(0, min(per, sg.k - w * per));
 
     const __bf16* kpool = (const __bf16*)a.c.k;
     const __bf16* vpool = (const __bf16*)a.c.v;
@@ -144,14 +144,7 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
         }
     }
 
-    const int n_pages_ctx = (ctx + PS - 1) >> 4;
-    int my_pid;
-    {
-        const int lp = min((wstart >> 4) + (lane & (2 * kSteps - 1)), n_pages_ctx - 1);
-        my_pid = a.bt[(int64_t)s * a.max_pages + lp];
-    }
-    const int n_steps = wstart < ctx ? min(wave_tok >> 5, (ctx - wstart + 31) >> 5) : 0;   // uniform over the wave
-
+    const int last_lp = ((ctx + PS - 1) >> 4) - 1;
     const float sl2 = a.scale * kLog2e;
     float m[R], lsum[R];
     f32x4 o[R][8];
@@ -170,9 +163,13 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
     const int v_pg = c >> 1;
     const int v_off = ((c & 1) * D + r) * 8;
 
-#pragma unroll
-    for (int st = 0; st < kSteps; ++st) {
-        if (st < n_steps) {
+    // the wave's steps in runs of 32 (64 pages: one physical page id per lane)
+#pragma unroll 1
+    for (int run = 0; run < my_n; run += 32) {
+        const int my_pid = a.bt[(int64_t)s * a.max_pages + min(2 * (my_u + run) + lane, last_lp)];
+        const int n_here = min(32, my_n - run);
+#pragma unroll 1
+        for (int st = 0; st < n_here; ++st) {
             StepRegs x;
             {
                 const int64_t pA = __builtin_amdgcn_readlane(my_pid, 2 * st);
@@ -186,11 +183,13 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
                 }
 #pragma unroll
                 for (int mb = 0; mb < 8; ++mb) x.v[mb] = ld16_stream(vp + mb * 16 * 8);
+                __builtin_amdgcn_sched_barrier(0);       // all 16 loads in flight before anything waits
             }
-            const int tok0 = wstart + st * 32;
+            const int tok0 = (my_u + run + st) * 32;
             const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
 #pragma unroll
             for (int j = 0; j < R; ++j) {
+                if (j > 0 && j * tq >= nt) break;        // a group without rows (a decode has one): uniform
                 f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kk = 0; kk < 4; ++kk) {
@@ -251,38 +250,38 @@ __device__ __forceinline__ void keys_item(const AttnArgs& a, float* __restrict__
         if (c == 0) { s_m[w][r] = m[j]; s_l[w][r] = l; }
         __syncthreads();
         const int n_cols = rows_here * G;
-        for (int idx = threadIdx.x; idx < n_cols * D; idx += 256) {
-            const int col = idx >> 7, d = idx & (D - 1);
-            float ms = s_m[0][col];
+        if (sg.piece < pmax) {
+            for (int idx = threadIdx.x; idx < n_cols * D; idx += 256) {
+                const int col = idx >> 7, d = idx & (D - 1);
+                float ms = s_m[0][col];
 #pragma unroll
-            for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][col]);
-            float acc = 0.f, lt = 0.f;
+                for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][col]);
+                float acc = 0.f, lt = 0.f;
 #pragma unroll
-            for (int ww = 0; ww < 4; ++ww) {
-                const float mw = s_m[ww][col];
-                const float f = mw == -INFINITY ? 0.f : exp2f(mw - ms);    // a wave that saw no key of this column
-                acc += f * s_o[ww][col][d];
-                lt += f * s_l[ww][col];
+                for (int ww = 0; ww < 4; ++ww) {
+                    const float mw = s_m[ww][col];
+                    const float f = mw == -INFINITY ? 0.f : exp2f(mw - ms);    // a wave that saw no key of this column
+                    acc += f * s_o[ww][col][d];
+                    lt += f * s_l[ww][col];
+                }
+                const int crow = col / G, chead = col - crow * G;
+                const int64_t slot = (((int64_t)a.cu_new[s] + t0 + j * tq + crow) * hq + (int64_t)g * G + chead) * pmax + sg.piece;
+                ws_o[slot * D + d] = acc;
+                if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = lt; }
             }
-            const int crow = col / G, chead = col - crow * G;
-            const int64_t slot = (((int64_t)a.cu_new[s] + t0 + j * tq + crow) * hq + (int64_t)g * G + chead) * n_splits_max + split;
-            ws_o[slot * D + d] = acc;
-            if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = lt; }
         }
     }
+    __syncthreads();                                         // the next segment writes the same LDS
 }
 
-// ---- rows item: four waves x 32 columns over the same keys, in the prefill kernel's 64-key tiles ---------------
+// ---- a segment of a rows item: four waves x 32 columns over the same keys, in the prefill kernel's tiles --------
 // Wave w holds column groups 2w and 2w + 1 of the item (group j = tokens j * tq .. + tq - 1, column r of a group =
-// token r / G, head r % G): 32 columns, the B operand of the 32x32x16 products.  The part's keys are walked in
+// token r / G, head r % G): 32 columns, the B operand of the 32x32x16 products.  The segment's keys are walked in
 // tiles of 64 (four pages) that the workgroup brings into LDS by direct global-to-LDS loads - three K stages,
 // two V stages, tile layouts and software pipeline as in the prefill kernel (attn_tile32.h) - and every wave
-// writes the partial (m, l, O) of its columns for the part straight to the workspace.
-constexpr int kRowsLds = (tile32::kKStages + 2) * tile32::kTile;        // 80 KiB
-
-template <int kSteps>
-__device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
-                                          int n_splits_max, int tq, const ItemCtx& it, unsigned char* lds)
+// writes the partial (m, l, O) of its columns for the segment straight to the workspace.
+__device__ __forceinline__ void tile_segment(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
+                                             int pmax, int tq, const Seg& it, unsigned char* lds)
 {
     using tile32::BN;
     using tile32::kKStages;
@@ -294,10 +293,8 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     const int wu = __builtin_amdgcn_readfirstlane(w);           // the same value, known to be uniform
     const int n = lane & 31, hi = lane >> 5;
 
-    // key tiles of the part: absolute tiles tb .. tb + n_tiles - 1 (parts start at multiples of 128 keys)
-    const int end = min(it.ctx, it.start + it.part);
-    const int tb = it.start / BN;
-    const int n_tiles = (end - 1) / BN + 1 - tb;                 // >= 1
+    // key tiles of the segment: tiles tb .. tb + n_tiles - 1 of the keys the item's last row may see
+    const int tb = it.u, n_tiles = it.k;                          // >= 1
 
     // this lane's column; columns without a row carry the item's last row (their results are not stored)
     const int r = n & 15;
@@ -308,7 +305,7 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     const int qpos = P + t0 + row;                               // logical position of this lane's query
     const int w_first = 2 * w * tq;                              // the wave's first token
     const int w_last = min(nt, w_first + 2 * tq) - 1;            // ... and last
-    // tiles of the part this wave uses (none if it has no rows, or if the part lies above all of them), and the
+    // tiles of the segment this wave uses (none if it has no rows, or if the segment lies above all of them), and the
     // first tile holding a key its first row may not see
     const int wave_tiles = w_first < nt ? max(0, min(n_tiles, (P + t0 + w_last) / BN + 1 - tb)) : 0;
     const int first_masked = (P + t0 + w_first + 1) / BN - tb;
@@ -434,8 +431,8 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     // o[mb][q4 * 4 + e] is O^T[channel mb * 32 + q4 * 8 + hi * 4 + e][column n]; m is shared by the two lanes of a
     // column, l is the sum of both
     lsum += __shfl_xor(lsum, 32);
-    if (on) {
-        const int64_t slot = (((int64_t)a.cu_new[s] + t0 + token) * hq + (int64_t)g * G + col_head) * n_splits_max + it.split;
+    if (on && it.piece < pmax) {
+        const int64_t slot = (((int64_t)a.cu_new[s] + t0 + token) * hq + (int64_t)g * G + col_head) * pmax + it.piece;
 #pragma unroll
         for (int mb = 0; mb < 4; ++mb)
 #pragma unroll
@@ -447,106 +444,255 @@ __device__ __forceinline__ void rows_item(const AttnArgs& a, float* __restrict__
     }
 }
 
-// kSteps: the split size is 128 * kSteps keys.  R: column groups per wave.  kRows: the launch has rows items.
-template <int kSteps, int R, bool kRows>
-__global__ __launch_bounds__(256, R == 1 ? 4 : 2) void merged_split_kernel(AttnArgs a, float* __restrict__ ws_o,
-                                                                           float* __restrict__ ws_ml,
-                                                                           const int32_t* __restrict__ plan,
-                                                                           int n_splits_max, int tq)
+// R: column groups per wave of a keys item.  kRows: the launch has rows items.
+// hdr[0], hdr[1]: the share sizes (steps per streaming workgroup, tiles per tile workgroup), for the merge kernel.
+template <int R, bool kRows>
+__global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, int32_t* __restrict__ hdr,
+                                                                           RowInfo* __restrict__ row_info,
+                                                                           float* __restrict__ ws_o,
+                                                                           float* __restrict__ ws_ml, int pmax,
+                                                                           int tq, int rk, int rw, float steps_per_us)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];     // kSmemBytes, or kRowsLds with rows items
-    const int item = blockIdx.z;
-    if (item >= plan[0]) return;
-    const int32_t* e = plan + 4 + 4 * item;
-    ItemCtx it;
-    it.s = e[0]; it.t0 = e[1]; it.nt = e[2];
-    const int kind = e[3];
-    // Workgroups go to the XCDs round-robin in linear order (x fastest).  The split is blockIdx.x rotated by
-    // head and session: short sessions only have the low split numbers, which would otherwise pile up on the
-    // XCDs that draw them (see the decode step); rotating by the session, not the item, keeps the items of one
-    // (session, KV head, split) on one XCD, whose L2 then serves what they fetch again.
-    it.g = blockIdx.y;
-    it.split = (int)((blockIdx.x + blockIdx.y + (unsigned)it.s) % gridDim.x);
-    const int N = a.new_lens[it.s];
-    it.P = a.prefix_lens ? a.prefix_lens[it.s] : 0;
-    it.ctx_all = it.P + N;                           // slots below this hold tokens
-    it.ctx = it.P + it.t0 + it.nt;                   // keys the item's last row may see
-    it.part = part_tokens(it.ctx, 128 * kSteps);
-    it.start = it.split * it.part;
-    if (it.start >= it.ctx) return;                  // uniform over the workgroup
-    if constexpr (kRows) {
-        if (kind == kRowsItem) { rows_item<kSteps>(a, ws_o, ws_ml, n_splits_max, tq, it, smem); return; }
+    // The plan's few words of LDS lie in the same buffer as the segments' data (two workgroups of 80 KiB fill a
+    // CU's LDS exactly); a barrier separates the plan's last read from the first segment.
+    int (*s_red)[4] = reinterpret_cast<int (*)[4]>(smem);                     // [2][4]
+    int* s_start = reinterpret_cast<int*>(smem) + 8;    // session holding the workgroup's first unit, units before it, N, P
+
+    const int B = a.batch, hkv = a.c.hkv;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int W = gridDim.x;
+    auto lengths = [&](int s, int& N, int& P) {
+        N = s < B ? a.new_lens[s] : 0;
+        P = (s < B && a.prefix_lens) ? a.prefix_lens[s] : 0;
+    };
+
+    // ---- the plan: totals of both kinds, the split of the workgroups, the two share sizes, where this
+    // workgroup's share starts.  One pass over the lengths when the batch fits it (the scan's totals are the
+    // totals); a larger batch is summed first. ----
+    int tot_k = 0, tot_t = 0;
+    if (B > 256) {
+        int lk = 0, lt = 0;
+        for (int s = tid; s < B; s += 256) {
+            int N, P;
+            lengths(s, N, P);
+            const Cut c = cut_of(N, rk, rw);
+            lk += session_steps(c, P);
+            if (kRows) lt += session_tiles(c, N, P, rw);
+        }
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) { lk += __shfl_xor(lk, d); lt += __shfl_xor(lt, d); }
+        if (lane == 0) { s_red[0][w] = lk; s_red[1][w] = lt; }
+        __syncthreads();
+        tot_k = s_red[0][0] + s_red[0][1] + s_red[0][2] + s_red[0][3];
+        tot_t = s_red[1][0] + s_red[1][1] + s_red[1][2] + s_red[1][3];
+        __syncthreads();
     }
-    keys_item<kSteps, R>(a, ws_o, ws_ml, n_splits_max, tq, it, smem);
+    const bool first_wg = blockIdx.x == 0;
+    int F_K = 0, F_T = 0, W_T = 0, q_K = kMinSteps, q_T = kMinTiles, me = 0, f0 = 0, f1 = 0;
+    bool tiles = false, active = false;
+    if (tid == 0) s_start[0] = B;           // (no session: nothing runs; cannot happen while the lengths stand still)
+    {
+        int carry_k = 0, carry_t = 0;       // units of the sessions before this pass of 256
+        for (int s0 = 0; s0 < B; s0 += 256) {
+            const int s = s0 + tid;
+            int N, P;
+            lengths(s, N, P);
+            const Cut c = cut_of(N, rk, rw);
+            const int nk = session_steps(c, P), nt = kRows ? session_tiles(c, N, P, rw) : 0;
+            int ik = nk, it = nt;           // inclusive scans over the wave
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const int tk = __shfl_up(ik, d), tt = __shfl_up(it, d);
+                if (lane >= d) { ik += tk; it += tt; }
+            }
+            if (lane == 63) { s_red[0][w] = ik; s_red[1][w] = it; }
+            __syncthreads();
+            int off_k = 0, off_t = 0;
+            for (int ww = 0; ww < w; ++ww) { off_k += s_red[0][ww]; off_t += s_red[1][ww]; }
+            const int pass_k = s_red[0][0] + s_red[0][1] + s_red[0][2] + s_red[0][3];
+            const int pass_t = s_red[1][0] + s_red[1][1] + s_red[1][2] + s_red[1][3];
+            if (s0 == 0) {                  // every value here is uniform over the workgroup
+                if (B <= 256) { tot_k = pass_k; tot_t = pass_t; }
+                F_K = hkv * tot_k;
+                F_T = kRows ? hkv * tot_t : 0;
+                if (F_K + F_T == 0) return;
+                // W_T so that both kinds end together.  While the streaming workgroups left over still saturate
+                // the memory system, the steps take F_K / steps_per_us whatever their number, and the tiles get
+                // the workgroups that finish them in that time; otherwise every workgroup is busy for the whole
+                // launch, and the workgroups are divided as the slot-times of the two kinds.
+                if (F_T > 0) {
+                    if (F_K == 0) {
+                        W_T = W;
+                    } else {
+                        const float tile_us = kTileUs * (float)F_T;
+                        float wt = tile_us * steps_per_us / (float)F_K;
+                        if ((float)W - wt < steps_per_us * kStepUsAlone) wt = (float)W * tile_us / (tile_us + kStepUsAlone * (float)F_K);
+                        W_T = max(1, min(W - 1, (int)(wt + 0.5f)));
+                    }
+                }
+                const int W_K = W - W_T;
+                if (F_K > 0) q_K = max(kMinSteps, (F_K + W_K - 1) / W_K);
+                if (F_T > 0) q_T = max(kMinTiles, (F_T + W_T - 1) / W_T);
+                if (first_wg && tid == 0) { hdr[0] = q_K; hdr[1] = q_T; }
+                // this workgroup's share: the tile workgroups come first in the grid
+                tiles = (int)blockIdx.x < W_T;
+                me = tiles ? blockIdx.x : blockIdx.x - W_T;       // number among the workgroups of its kind
+                const int q = tiles ? q_T : q_K, F = tiles ? F_T : F_K;
+                f0 = me * q;
+                f1 = min(f0 + q, F);
+                active = f0 < F;
+                if (!active && !first_wg) return;
+            }
+            const int excl_k = carry_k + off_k + ik - nk, excl_t = carry_t + off_t + it - nt;
+            const int mine = tiles ? nt : nk, excl = tiles ? excl_t : excl_k;
+            if (active && mine > 0 && hkv * excl <= f0 && f0 < hkv * (excl + mine)) {
+                s_start[0] = s; s_start[1] = excl; s_start[2] = N; s_start[3] = P;
+            }
+            if (first_wg && s < B) {        // the first workgroup also publishes the rows' plan for the merge kernel
+                const int row0 = a.cu_new[s];
+                int acc = 0;                // tiles of the session's earlier rows items
+                for (int j = 0; j < c.n_rows_items; ++j) {
+                    const int tj = item_tiles(N, P, rw, j);
+                    for (int x = j * rw; x < min(N, (j + 1) * rw); ++x)
+                        if (row0 + x < a.total_rows) row_info[row0 + x] = RowInfo{kRowsItem, hkv * excl_t + acc, nt, tj};
+                    acc += tj;
+                }
+                for (int x = c.k_t0; x < c.k_t0 + c.k_nt; ++x)
+                    if (row0 + x < a.total_rows) row_info[row0 + x] = RowInfo{kKeysItem, hkv * excl_k, nk, nk};
+            }
+            __syncthreads();
+            carry_k += pass_k;
+            carry_t += pass_t;
+            if (!first_wg && hkv * (tiles ? carry_t : carry_k) > f0) break;       // found (uniform)
+        }
+    }
+    if (!active) return;
+    int s = s_start[0];
+    int base = hkv * s_start[1];            // flat unit at which session s starts
+    int N = s_start[2], P = s_start[3];
+    Cut c = cut_of(N, rk, rw);
+    __syncthreads();                        // the segments reuse the plan's LDS
+
+    if (!tiles) {
+        // ---- streaming share: segments of (session, KV head) pairs, n steps each ----
+        int n = session_steps(c, P);
+        int g = (f0 - base) / n;
+        int u = (f0 - base) - g * n;
+        for (int f = f0; f < f1 && s < B;) {                 // one segment per pass; every value here is uniform
+            const int k = min(n - u, f1 - f);
+            if (k <= 0) break;                               // (only if the lengths changed under the kernel: never spin)
+            Seg sg;
+            sg.s = s; sg.g = g; sg.t0 = c.k_t0; sg.nt = c.k_nt; sg.P = P; sg.ctx_all = P + N; sg.ctx = P + c.k_t0 + c.k_nt;
+            sg.u = u; sg.k = k;
+            sg.piece = me - (base + g * n) / q_K;            // the pair's partials are numbered from its first workgroup
+            stream_segment<R>(a, ws_o, ws_ml, pmax, tq, sg, smem);
+            f += k;
+            u += k;
+            if (u == n) {                                    // on to the next pair
+                u = 0;
+                if (++g == hkv) {
+                    g = 0;
+                    base += hkv * n;
+                    do {
+                        ++s;
+                        lengths(s, N, P);
+                        c = cut_of(N, rk, rw);
+                        n = session_steps(c, P);
+                    } while (s < B && n == 0);
+                }
+            }
+        }
+    } else if constexpr (kRows) {
+        // ---- tile share: segments of (session, KV head, rows item) triples; a session has n tiles per KV head ----
+        int n = session_tiles(c, N, P, rw);
+        int g = (f0 - base) / n;
+        int u = (f0 - base) - g * n;        // first tile inside (s, g): find the item it falls in
+        int j = 0, before = 0;              // ... and the tiles of the items before it
+        for (;;) {
+            const int tj = item_tiles(N, P, rw, j);
+            if (u < tj || j + 1 >= c.n_rows_items) break;
+            u -= tj; before += tj; ++j;
+        }
+        for (int f = f0; f < f1 && s < B;) {
+            const int tj = item_tiles(N, P, rw, j);
+            const int k = min(tj - u, f1 - f);
+            if (k <= 0) break;
+            Seg sg;
+            sg.s = s; sg.g = g; sg.t0 = j * rw; sg.nt = min(rw, N - j * rw); sg.P = P; sg.ctx_all = P + N;
+            sg.ctx = P + sg.t0 + sg.nt;
+            sg.u = u; sg.k = k;
+            sg.piece = me - (base + g * n + before) / q_T;
+            tile_segment(a, ws_o, ws_ml, pmax, tq, sg, smem);
+            f += k;
+            u += k;
+            if (u == tj) {                                   // on to the next item, head, session
+                u = 0;
+                before += tj;
+                if (++j == c.n_rows_items) {
+                    j = 0;
+                    before = 0;
+                    if (++g == hkv) {
+                        g = 0;
+                        base += hkv * n;
+                        do {
+                            ++s;
+                            lengths(s, N, P);
+                            c = cut_of(N, rk, rw);
+                            n = session_tiles(c, N, P, rw);
+                        } while (s < B && n == 0);
+                    }
+                }
+            }
+        }
+    }
 }
 
-__global__ __launch_bounds__(128) void merged_merge_kernel(AttnArgs a, const float* __restrict__ ws_o,
-                                                           const float* __restrict__ ws_ml,
-                                                           const int32_t* __restrict__ row_ctx, int n_splits_max,
-                                                           int split_tokens)
+// Two (row, head) pairs per workgroup: the pair's partials are those of the workgroups its units were dealt to.
+__global__ __launch_bounds__(256) void merged_merge_kernel(AttnArgs a, const int32_t* __restrict__ hdr,
+                                                           const RowInfo* __restrict__ row_info,
+                                                           const float* __restrict__ ws_o,
+                                                           const float* __restrict__ ws_ml, int pmax)
 {
-    const int64_t rh = blockIdx.x;                 // row * hq + head
-    const int row = (int)(rh / a.hq);
-    const int d = threadIdx.x;
-    const int ctx = row_ctx[row];                  // as the split kernel cut the row's item
-    const int part = part_tokens(ctx, split_tokens);
-    const int n = (ctx + part - 1) / part;
-    ((__bf16*)a.out)[rh * D + d] = (__bf16)merge_partials(ws_o, ws_ml, rh * n_splits_max, n, d);
+    const int64_t rh = (int64_t)blockIdx.x * 2 + (threadIdx.x >> 7);        // row * hq + head
+    if (rh >= (int64_t)a.total_rows * a.hq) return;
+    const int row = (int)(rh / a.hq), head = (int)(rh - (int64_t)row * a.hq);
+    const int d = threadIdx.x & 127;
+    const RowInfo ri = row_info[row];
+    const int q = max(1, hdr[ri.kind == kRowsItem ? 1 : 0]);
+    const int first = ri.first + (head / (a.hq / a.c.hkv)) * ri.stride;
+    const int pieces = min(pmax, (first + ri.n - 1) / q - first / q + 1);
+    ((__bf16*)a.out)[rh * D + d] = (__bf16)merge_partials(ws_o, ws_ml, rh * pmax, pieces, d);
 }
 
 inline int rows_per_group(int hq, int hkv) { return 16 / (hq / hkv); }
 
-inline int choose_split(int64_t items, int hkv, int max_ctx, int largest)
-{
-    // As long as possible (every workgroup pays a fixed start-up) while the launch still has about eight
-    // workgroups per CU, counting contexts at about 60 % of max_ctx: a queue that mixes a few long resume
-    // prefixes with many shorter decode contexts is far below that estimate, and one round of long workgroups
-    // balances badly.
-    const int64_t want = 8 * 256;
-    for (int split = largest; split > kMinSplit; split >>= 1) {
-        const int64_t wgs = items * hkv * ((6 * (int64_t)max_ctx / 10 + split - 1) / split);
-        if (wgs >= want) return split;
-    }
-    return kMinSplit;
-}
-
-struct Layout { size_t o_floats, ml_floats, plan_ints, row_ints; };
+struct Layout { size_t o_floats, ml_floats, hdr_ints, row_ints; };
 inline Layout layout(int total_rows, int hq, int max_ctx)
 {
-    const size_t nsm = (size_t)splits_for(max_ctx, kMinSplit);
-    return {(size_t)total_rows * hq * nsm * D, (size_t)total_rows * hq * nsm * 2, 4 + 4 * (size_t)total_rows, (size_t)total_rows};
+    const size_t pm = (size_t)pieces_max(max_ctx);
+    return {(size_t)total_rows * hq * pm * D, ((size_t)total_rows * hq * pm * 2 + 3) & ~(size_t)3, 4, 4 * (size_t)total_rows};
 }
 
-template <int kSteps, int R, bool kRows>
-ag_status launch_one(dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml, const int32_t* plan, int nsm, int tq)
+template <int R, bool kRows>
+ag_status launch_split(int n_wgs, hipStream_t st, const AttnArgs& a, int32_t* hdr, RowInfo* row_info, float* ws_o,
+                       float* ws_ml, int pmax, int tq, int rk, int rw, float steps_per_us)
 {
     constexpr int lds = kRows ? kRowsLds : kSmemBytes;
     if constexpr (kRows) {                  // more dynamic LDS than a kernel may use without being told so
         static std::atomic<bool> attr_set{false};
         if (!attr_set.load()) {
-            ag_status e = hip_check(hipFuncSetAttribute((const void*)merged_split_kernel<kSteps, R, kRows>,
+            ag_status e = hip_check(hipFuncSetAttribute((const void*)merged_split_kernel<R, kRows>,
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds),
                                     "hipFuncSetAttribute(merged split)");
             if (e) return e;
             attr_set.store(true);
         }
     }
-    hipLaunchKernelGGL((merged_split_kernel<kSteps, R, kRows>), grid, dim3(256), lds, st, a, ws_o, ws_ml, plan, nsm, tq);
+    hipLaunchKernelGGL((merged_split_kernel<R, kRows>), dim3((unsigned)n_wgs), dim3(256), lds, st, a, hdr, row_info, ws_o,
+                       ws_ml, pmax, tq, rk, rw, steps_per_us);
     return AG_OK;
-}
-
-template <int R, bool kRows>
-ag_status launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, float* ws_o, float* ws_ml,
-                       const int32_t* plan, int nsm, int tq)
-{
-    switch (split) {
-        case 2048:
-            if constexpr (!kRows) return launch_one<16, R, false>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-            [[fallthrough]];     // not chosen for launches with rows items
-        case 1024: return launch_one<8, R, kRows>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-        case 512:  return launch_one<4, R, kRows>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-        default:   return launch_one<2, R, kRows>(grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-    }
 }
 
 }  // namespace
@@ -554,7 +700,7 @@ ag_status launch_split(int split, dim3 grid, hipStream_t st, const AttnArgs& a, 
 size_t merged_workspace_bytes(int total_rows, int hq, int max_ctx)
 {
     const Layout L = layout(total_rows, hq, max_ctx);
-    return (L.o_floats + L.ml_floats + L.plan_ints + L.row_ints) * 4;
+    return (L.o_floats + L.ml_floats + L.hdr_ints + L.row_ints) * 4;
 }
 
 bool merged_mfma_supported(const AttnArgs& a)
@@ -568,37 +714,35 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
     if (a.total_rows <= 0) return AG_OK;
     const int tq = rows_per_group(a.hq, a.c.hkv);
-    // A batch of decodes only (no session brings more rows than one group holds): one group per item, four
-    // waves per SIMD.  Otherwise two groups per wave: keys items of up to 2 tq rows, and - once some session
+    // A batch of decodes only (no session brings more rows than one group holds): one group per keys item.
+    // Otherwise two groups per wave: keys items of up to 2 tq rows, and - once some session
     // may bring more than that - rows items of up to 8 tq rows.
     const int R = a.max_new > tq ? 2 : 1;
     const bool rows = a.max_new > R * tq;
-    const int rk = R * tq, rw = rows ? 4 * R * tq : 0;
-    // a session of N rows has at most N / (rows per full item) + 1 items, and every item has at least one row
-    const int64_t items_max = std::min<int64_t>(a.total_rows, (int64_t)a.total_rows / (rw ? rw : rk) + a.batch);
-    if (items_max > 65535 || a.c.hkv > 65535) { set_error("too many items (%lld) or KV heads for one launch grid", (long long)items_max); return AG_ERR_INVALID_ARG; }
-    const int split = choose_split(items_max, a.c.hkv, a.max_ctx, rows ? 1024 : 2048);
-    const int nsm = splits_for(a.max_ctx, split);
+    const int rk = R * tq, rw = rows ? 8 * tq : 0;
     const Layout L = layout(a.total_rows, a.hq, a.max_ctx);
+    const int pmax = pieces_max(a.max_ctx);
     float* ws_o = (float*)ws;
     float* ws_ml = ws_o + L.o_floats;
-    int32_t* plan = (int32_t*)(ws_ml + L.ml_floats);
-    int32_t* row_ctx = plan + L.plan_ints;
+    int32_t* hdr = (int32_t*)(ws_ml + L.ml_floats);
+    RowInfo* row_info = (RowInfo*)(hdr + L.hdr_ints);
+    // As many workgroups as the stream's CUs hold at once (paper Sec. III-C: the decode queue runs on a partition).
+    // The steps the stream's CUs can move per microsecond: the device's rate, or what its CUs can draw if that
+    // is less (two workgroups per CU at 0.57 us a step each).
+    const int cus = stream_cus(st);
+    const int n_wgs = 2 * cus;      // equal shares: as few workgroups as fill every CU evenly, as in the decode step
+    const float steps_per_us = std::min(kDeviceStepsPerUs * (float)device_cus() / 256.0f, 2.0f * (float)cus / kStepUsAlone);
 
-    hipLaunchKernelGGL(merged_plan_kernel, dim3(1), dim3(256), 0, st, a.new_lens, a.prefix_lens, a.cu_new, a.batch,
-                       a.total_rows, rk, rw, plan, row_ctx);
-    ag_status e = hip_check(hipGetLastError(), "merged plan launch");
-    if (e) return e;
-    const dim3 grid(nsm, a.c.hkv, (unsigned)items_max);
     prof_before(st);
-    if (R == 1) e = launch_split<1, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-    else if (!rows) e = launch_split<2, false>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
-    else e = launch_split<2, true>(split, grid, st, a, ws_o, ws_ml, plan, nsm, tq);
+    ag_status e;
+    if (R == 1) e = launch_split<1, false>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
+    else if (!rows) e = launch_split<2, false>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
+    else e = launch_split<2, true>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
     prof_after(st);
     if (e) return e;
     if ((e = hip_check(hipGetLastError(), "merged split launch"))) return e;
-    hipLaunchKernelGGL(merged_merge_kernel, dim3((unsigned)((int64_t)a.total_rows * a.hq)), dim3(128), 0, st, a, ws_o, ws_ml,
-                       row_ctx, nsm, split);
+    const int64_t pairs = (int64_t)a.total_rows * a.hq;
+    hipLaunchKernelGGL(merged_merge_kernel, dim3((unsigned)((pairs + 1) / 2)), dim3(256), 0, st, a, hdr, row_info, ws_o, ws_ml, pmax);
     return hip_check(hipGetLastError(), "merged merge launch");
 }
 
