@@ -137,10 +137,11 @@ static ag_status prefill_common(const ag_kv_cache* cache, const void* q, void* o
     a.prefix_lens = prefix_lens; a.new_lens = new_lens; a.cu_new = cu_new; a.ctx_lens = nullptr;
     a.batch = batch; a.total_rows = total_new; a.max_new = max_new; a.max_ctx = max_ctx; a.hq = hq; a.scale = scale;
     if (merged) {
-        // The decode-step schedule of the merged kernel pays while the queue's chunks are short; once some chunk
-        // has about a hundred rows the prefill kernel's tiles are faster even with the decodes in the same launch
-        // (measured crossover between 64 and 128 rows per chunk), and the semantics are the same.
-        constexpr int kMergedRowsLimit = 96;
+        // The merged kernel cuts a chunk into items of 32 rows (at G = 4), each of which walks the chunk's whole
+        // prefix; once chunks are long the prefill kernel's larger tiles are faster even with the decodes in the
+        // same launch (64 decodes + 8 chunks on 2-8k-token prefixes: 237 against 248 us at 128 rows per chunk, 294
+        // against 268 us at 192), and the semantics are the same.
+        constexpr int kMergedRowsLimit = 144;
         if (max_new >= kMergedRowsLimit && prefill_mfma_supported(a)) return launch_prefill_mfma(a, (hipStream_t)stream);
         if (merged_mfma_supported(a)) return launch_merged_mfma(a, workspace, (hipStream_t)stream);
         return launch_attn_general(a, (hipStream_t)stream);
