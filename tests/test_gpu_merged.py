@@ -83,6 +83,41 @@ def test_merged_long_context_many_splits():
     check_close(gpu_merged(cache, DevBatch(chunk)), oracle_attn(kp, vp, chunk), g.dtype, "30k context")
 
 
+def test_merged_on_a_small_partition_shares_span_several_runs_of_page_ids():
+    """On 8 CUs the launch has 16 workgroups, so a share is hundreds of steps (a wave's steps then come in several
+    runs of 64 pages) and tens of tiles, and crosses sessions, heads and items."""
+    g = geom(pages=4096, hq=8, hkv=2)
+    cache, kp, vp, chunk = filled(g, [30000, 12345, 5000, 0], [6, 1, 70, 1], seed=15)
+    d = DevBatch(chunk)
+    ref = oracle_attn(kp, vp, chunk)
+    info = B.ag_device_info()
+    total, n_xcd = info["num_cus"], info["num_xcd"] or 8
+    st = B.ag_stream_create_cumask(B.ag_cumask_build(total, n_xcd, 0, 1))
+    try:
+        ws = torch.full((B.ag_attn_merged_workspace_bytes(d.total, g.num_q_heads, d.max_ctx) // 4,), float("nan"),
+                        dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        B.ag_attn_merged(cache, d.q, d.out, d.bt, d.prefix, d.new, d.cu, d.total, d.max_new, d.max_ctx,
+                         g.num_q_heads, g.scale, ws, stream=st)
+        torch.cuda.synchronize()
+    finally:
+        B.ag_stream_destroy(st)
+    check_close(to_f64(d.out, g.dtype), ref, g.dtype, "8-CU partition")
+    check_close(gpu_merged(cache, d), ref, g.dtype, "whole device, same batch")
+
+
+def test_merged_more_sessions_than_one_pass_of_the_plan():
+    """300 sessions (the plan scans 256 at a time): decodes, empty sessions, short and long chunks in any order."""
+    g = geom(pages=8192, hq=8, hkv=2)
+    rng = I.rng_for(4242, 0)
+    prefix = [int(x) for x in rng.integers(0, 400, size=300)]
+    new = [int(x) for x in rng.choice([0, 1, 1, 1, 1, 2, 5, 9, 17, 40], size=300)]
+    prefix[7], new[7] = 0, 33                          # a cold-like chunk
+    prefix[290], new[290] = 2500, 1                    # a long decode behind the first pass
+    cache, kp, vp, chunk = filled(g, prefix, new, seed=91)
+    check_close(gpu_merged(cache, DevBatch(chunk)), oracle_attn(kp, vp, chunk), g.dtype, "300 sessions")
+
+
 def test_merged_names_the_planted_key_under_the_causal_limit():
     """Each row's query points at one key; rows of one item differ in which keys they may see, so a wrong
     per-column limit (the item's instead of the row's) would let a row name a key from its future."""
