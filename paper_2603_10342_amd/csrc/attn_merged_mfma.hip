@@ -7,16 +7,16 @@
 // workgroups, partial (m, l, O) per cut, merged in cut order, as in the decode step, because with few rows per
 // session the launch is bound by reading K and V.  A session's rows are cut into items of two kinds:
 //
-//   keys item  up to R groups of rows (a group is tq = 16 / G consecutive rows, G = query heads per KV head: its
+//   keys item  one group of rows (a group is tq = 16 / G consecutive rows, G = query heads per KV head: its
 //              tq x G (row, head) pairs fill the 16 columns of the matrix instruction that a decode leaves mostly
 //              empty).  Work on it streams: the four waves of a workgroup split the keys, each K / V step
-//              (32 keys) is loaded once into registers for the R groups - the decode step's loop with a
-//              visibility limit per column.  Bound by memory.
+//              (32 keys) is loaded once into registers - the decode step's loop with a visibility limit per
+//              column.  Bound by memory.
 //   rows item  up to 8 groups of rows (32 rows at G = 4): four waves x 32 columns walk the same keys in the
 //              prefill kernel's 64-key tiles, which the workgroup brings into LDS once (attn_tile32.h), so the
 //              keys are fetched once per 8 groups.  Bound by the matrix cores.
-//   A session has full rows items and a remainder that is a keys item if it has at most R groups of rows, else one
-//   more rows item; a decode, or any chunk of at most R groups, is one keys item.
+//   A session has full rows items and a remainder that is a keys item if it fits one group, else one more rows
+//   item; a decode, or any chunk of at most tq rows, is one keys item.
 //
 // The launch has exactly as many workgroups as the stream's CUs hold at once, and no planning launch: as in the
 // decode step, the work of each kind is laid end to end - the keys items' (session, KV head) pairs in steps of 32
@@ -102,12 +102,11 @@ struct Seg {
     int piece;              // which of the pair's partials this segment leaves
 };
 
-// ---- a segment of a keys item: the decode step's loop with R column groups -----------------------------------
-template <int R>
+// ---- a segment of a keys item: the decode step's loop with a visibility limit per column ----------------------
 __device__ __forceinline__ void stream_segment(const AttnArgs& a, float* __restrict__ ws_o, float* __restrict__ ws_ml,
                                                int pmax, int tq, const Seg& sg, unsigned char* smem)
 {
-    float (*s_o)[16][D] = reinterpret_cast<float (*)[16][D]>(smem);                 // per wave, per column of one group
+    float (*s_o)[16][D] = reinterpret_cast<float (*)[16][D]>(smem);                 // per wave, per column
     float (*s_m)[16] = reinterpret_cast<float (*)[16]>(smem + 4 * 16 * D * 4);
     float (*s_l)[16] = s_m + 4;
 
@@ -124,37 +123,29 @@ __device__ __forceinline__ void stream_segment(const AttnArgs& a, float* __restr
     const __bf16* kpool = (const __bf16*)a.c.k;
     const __bf16* vpool = (const __bf16*)a.c.v;
 
-    // column r of group j = (row j * tq + r / G of the item, head r % G of the KV head's group); columns
-    // without a row carry a zero query and the visibility of the item's last row
+    // column r = (row r / G of the item, head r % G of the KV head's group); columns without a row carry a zero
+    // query and the visibility of the item's last row
     const int col_row = r / G, col_head = r - col_row * G;
-    int pos[R];
-    bf16x8 qf[R][4];
-#pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int row = j * tq + col_row;
-        const bool on = col_row < tq && row < nt;
-        pos[j] = P + t0 + (on ? row : nt - 1);
-        const int64_t q_row = (int64_t)a.cu_new[s] + t0 + (on ? row : 0);
+    const bool on = col_row < tq && col_row < nt;
+    const int pos = P + t0 + (on ? col_row : nt - 1);
+    bf16x8 qf[4];
+    {
+        const int64_t q_row = (int64_t)a.cu_new[s] + t0 + (on ? col_row : 0);
         const __bf16* qrow = (const __bf16*)a.q + (q_row * hq + (int64_t)g * G + col_head) * D + c * 8;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             bf16x8 x = ld16(qrow + kk * 32);
             if (!on) x = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
-            qf[j][kk] = x;
+            qf[kk] = x;
         }
     }
 
     const int last_lp = ((ctx + PS - 1) >> 4) - 1;
     const float sl2 = a.scale * kLog2e;
-    float m[R], lsum[R];
-    f32x4 o[R][8];
+    float m = -INFINITY, lsum = 0.0f;
+    f32x4 o[8];
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        m[j] = -INFINITY;
-        lsum[j] = 0.0f;
-#pragma unroll
-        for (int mb = 0; mb < 8; ++mb) o[j][mb] = f32x4{0.f, 0.f, 0.f, 0.f};
-    }
+    for (int mb = 0; mb < 8; ++mb) o[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // operand addressing as in the decode step: score row r is slot (r & 7) of page (r >> 3) of the step, the
     // second score product takes slots 8..15; lane group c owns the 8 keys of value chunk (c & 1) of page (c >> 1)
@@ -187,88 +178,76 @@ __device__ __forceinline__ void stream_segment(const AttnArgs& a, float* __restr
             }
             const int tok0 = (my_u + run + st) * 32;
             const int tokb = tok0 + (c >> 1) * PS + (c & 1) * 4;
+            f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int j = 0; j < R; ++j) {
-                if (j > 0 && j * tq >= nt) break;        // a group without rows (a decode has one): uniform
-                f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
+            for (int kk = 0; kk < 4; ++kk) {
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qf[kk], s1, 0, 0, 0);
+                s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qf[kk], s2, 0, 0, 0);
+            }
+            // s1[i]: key tokb + i, s2[i]: key tokb + 8 + i, of column r
+            const int keep = pos + 1 - tokb;         // key tokb + i is visible to this column iff i < keep
+            float xs[8];
 #pragma unroll
-                for (int kk = 0; kk < 4; ++kk) {
-                    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k1[kk], qf[j][kk], s1, 0, 0, 0);
-                    s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.k2[kk], qf[j][kk], s2, 0, 0, 0);
-                }
-                // s1[i]: key tokb + i, s2[i]: key tokb + 8 + i, of column r
-                const int keep = pos[j] + 1 - tokb;  // key tokb + i is visible to this column iff i < keep
-                float xs[8];
+            for (int i = 0; i < 4; ++i) {
+                xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
+                xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
+            }
+            float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            const float m_new = fmaxf(m, mx);
+            // a column may see none of this wave's keys so far (its row lies before them): keep the exponents finite
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
+            float psum = 0.f;
+            bf16x8 pb;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    xs[i] = (i < keep) ? s1[i] * sl2 : -INFINITY;
-                    xs[4 + i] = (8 + i < keep) ? s2[i] * sl2 : -INFINITY;
-                }
-                float mx = fmaxf(fmaxf(fmaxf(xs[0], xs[1]), fmaxf(xs[2], xs[3])), fmaxf(fmaxf(xs[4], xs[5]), fmaxf(xs[6], xs[7])));
-                mx = fmaxf(mx, __shfl_xor(mx, 16));
-                mx = fmaxf(mx, __shfl_xor(mx, 32));
-                const float m_new = fmaxf(m[j], mx);
-                // a column may see none of this wave's keys so far (its row lies before them): keep the exponents finite
-                const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-                const float alpha = __builtin_amdgcn_exp2f(m[j] - m_ref);
-                float psum = 0.f;
-                bf16x8 pb;
+            for (int e = 0; e < 8; ++e) {
+                const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
+                psum += p;
+                pb[e] = (__bf16)p;
+            }
+            lsum = lsum * alpha + psum;
+            m = m_new;
+            if (tok0 + 32 > ctx_all) {               // slots past the session's last token may hold anything, NaN included
+                const int keep_v = ctx_all - tokb;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float p = __builtin_amdgcn_exp2f(xs[e] - m_ref);
-                    psum += p;
-                    pb[e] = (__bf16)p;
-                }
-                lsum[j] = lsum[j] * alpha + psum;
-                m[j] = m_new;
-                if (j == 0 && tok0 + 32 > ctx_all) {   // slots past the session's last token may hold anything, NaN included
-                    const int keep_v = ctx_all - tokb;
+                for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep_v, keep_v - 8);
+            }
 #pragma unroll
-                    for (int mb = 0; mb < 8; ++mb) x.v[mb] = keep_quads(x.v[mb], keep_v, keep_v - 8);
-                }
-#pragma unroll
-                for (int mb = 0; mb < 8; ++mb) {
-                    o[j][mb] *= alpha;
-                    o[j][mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[j][mb], 0, 0, 0);
-                }
+            for (int mb = 0; mb < 8; ++mb) {
+                o[mb] *= alpha;
+                o[mb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(x.v[mb], pb, o[mb], 0, 0, 0);
             }
         }
     }
 
-    // the four waves' partials of one group at a time through LDS
+    // the four waves' partials through LDS; o[mb][i] is O^T[d = mb*16 + c*4 + i][column r]
+    lsum += __shfl_xor(lsum, 16);
+    lsum += __shfl_xor(lsum, 32);
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        const int rows_here = min(tq, nt - j * tq);          // rows of group j; uniform over the workgroup
-        if (rows_here <= 0) break;
-        float l = lsum[j];
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
-        if (j > 0) __syncthreads();                          // the previous group's readers are done
-        // o[j][mb][i] is O^T[d = mb*16 + c*4 + i][column r]
+    for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(&s_o[w][r][mb * 16 + c * 4]) = o[mb];
+    if (c == 0) { s_m[w][r] = m; s_l[w][r] = lsum; }
+    __syncthreads();
+    if (sg.piece < pmax) {
+        const int n_cols = min(tq, nt) * G;
+        for (int idx = threadIdx.x; idx < n_cols * D; idx += 256) {
+            const int col = idx >> 7, d = idx & (D - 1);
+            float ms = s_m[0][col];
 #pragma unroll
-        for (int mb = 0; mb < 8; ++mb) *reinterpret_cast<f32x4*>(&s_o[w][r][mb * 16 + c * 4]) = o[j][mb];
-        if (c == 0) { s_m[w][r] = m[j]; s_l[w][r] = l; }
-        __syncthreads();
-        const int n_cols = rows_here * G;
-        if (sg.piece < pmax) {
-            for (int idx = threadIdx.x; idx < n_cols * D; idx += 256) {
-                const int col = idx >> 7, d = idx & (D - 1);
-                float ms = s_m[0][col];
+            for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][col]);
+            float acc = 0.f, lt = 0.f;
 #pragma unroll
-                for (int ww = 1; ww < 4; ++ww) ms = fmaxf(ms, s_m[ww][col]);
-                float acc = 0.f, lt = 0.f;
-#pragma unroll
-                for (int ww = 0; ww < 4; ++ww) {
-                    const float mw = s_m[ww][col];
-                    const float f = mw == -INFINITY ? 0.f : exp2f(mw - ms);    // a wave that saw no key of this column
-                    acc += f * s_o[ww][col][d];
-                    lt += f * s_l[ww][col];
-                }
-                const int crow = col / G, chead = col - crow * G;
-                const int64_t slot = (((int64_t)a.cu_new[s] + t0 + j * tq + crow) * hq + (int64_t)g * G + chead) * pmax + sg.piece;
-                ws_o[slot * D + d] = acc;
-                if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = lt; }
+            for (int ww = 0; ww < 4; ++ww) {
+                const float mw = s_m[ww][col];
+                const float f = mw == -INFINITY ? 0.f : exp2f(mw - ms);    // a wave that saw no key of this column
+                acc += f * s_o[ww][col][d];
+                lt += f * s_l[ww][col];
             }
+            const int crow = col / G, chead = col - crow * G;
+            const int64_t slot = (((int64_t)a.cu_new[s] + t0 + crow) * hq + (int64_t)g * G + chead) * pmax + sg.piece;
+            ws_o[slot * D + d] = acc;
+            if (d == 0) { ws_ml[slot * 2] = ms; ws_ml[slot * 2 + 1] = lt; }
         }
     }
     __syncthreads();                                         // the next segment writes the same LDS
@@ -444,9 +423,9 @@ __device__ __forceinline__ void tile_segment(const AttnArgs& a, float* __restric
     }
 }
 
-// R: column groups per wave of a keys item.  kRows: the launch has rows items.
+// kRows: the launch has rows items.
 // hdr[0], hdr[1]: the share sizes (steps per streaming workgroup, tiles per tile workgroup), for the merge kernel.
-template <int R, bool kRows>
+template <bool kRows>
 __global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, int32_t* __restrict__ hdr,
                                                                            RowInfo* __restrict__ row_info,
                                                                            float* __restrict__ ws_o,
@@ -587,7 +566,7 @@ __global__ __launch_bounds__(256, 2) void merged_split_kernel(AttnArgs a, int32_
             sg.s = s; sg.g = g; sg.t0 = c.k_t0; sg.nt = c.k_nt; sg.P = P; sg.ctx_all = P + N; sg.ctx = P + c.k_t0 + c.k_nt;
             sg.u = u; sg.k = k;
             sg.piece = me - (base + g * n) / q_K;            // the pair's partials are numbered from its first workgroup
-            stream_segment<R>(a, ws_o, ws_ml, pmax, tq, sg, smem);
+            stream_segment(a, ws_o, ws_ml, pmax, tq, sg, smem);
             f += k;
             u += k;
             if (u == n) {                                    // on to the next pair
@@ -675,7 +654,7 @@ inline Layout layout(int total_rows, int hq, int max_ctx)
     return {(size_t)total_rows * hq * pm * D, ((size_t)total_rows * hq * pm * 2 + 3) & ~(size_t)3, 4, 4 * (size_t)total_rows};
 }
 
-template <int R, bool kRows>
+template <bool kRows>
 ag_status launch_split(int n_wgs, hipStream_t st, const AttnArgs& a, int32_t* hdr, RowInfo* row_info, float* ws_o,
                        float* ws_ml, int pmax, int tq, int rk, int rw, float steps_per_us)
 {
@@ -683,14 +662,14 @@ ag_status launch_split(int n_wgs, hipStream_t st, const AttnArgs& a, int32_t* hd
     if constexpr (kRows) {                  // more dynamic LDS than a kernel may use without being told so
         static std::atomic<bool> attr_set{false};
         if (!attr_set.load()) {
-            ag_status e = hip_check(hipFuncSetAttribute((const void*)merged_split_kernel<R, kRows>,
+            ag_status e = hip_check(hipFuncSetAttribute((const void*)merged_split_kernel<kRows>,
                                                         hipFuncAttributeMaxDynamicSharedMemorySize, lds),
                                     "hipFuncSetAttribute(merged split)");
             if (e) return e;
             attr_set.store(true);
         }
     }
-    hipLaunchKernelGGL((merged_split_kernel<R, kRows>), dim3((unsigned)n_wgs), dim3(256), lds, st, a, hdr, row_info, ws_o,
+    hipLaunchKernelGGL((merged_split_kernel<kRows>), dim3((unsigned)n_wgs), dim3(256), lds, st, a, hdr, row_info, ws_o,
                        ws_ml, pmax, tq, rk, rw, steps_per_us);
     return AG_OK;
 }
@@ -714,12 +693,12 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 {
     if (a.total_rows <= 0) return AG_OK;
     const int tq = rows_per_group(a.hq, a.c.hkv);
-    // A batch of decodes only (no session brings more rows than one group holds): one group per keys item.
-    // Otherwise two groups per wave: keys items of up to 2 tq rows, and - once some session
-    // may bring more than that - rows items of up to 8 tq rows.
-    const int R = a.max_new > tq ? 2 : 1;
-    const bool rows = a.max_new > R * tq;
-    const int rk = R * tq, rw = rows ? 8 * tq : 0;
+    // Keys items hold one group of rows (tq: a decode, or a chunk that fits the 16 columns with its heads); once
+    // some session may bring more, there are rows items of up to 8 groups.  (Keys items of two groups - the
+    // streaming loop with twice the arithmetic per step for every item, decodes included - measured 146 against
+    // 127 us on a queue of 64 decodes and 8 chunks of 8 rows.)
+    const bool rows = a.max_new > tq;
+    const int rk = tq, rw = rows ? 8 * tq : 0;
     const Layout L = layout(a.total_rows, a.hq, a.max_ctx);
     const int pmax = pieces_max(a.max_ctx);
     float* ws_o = (float*)ws;
@@ -735,9 +714,8 @@ ag_status launch_merged_mfma(const AttnArgs& a, void* ws, hipStream_t st)
 
     prof_before(st);
     ag_status e;
-    if (R == 1) e = launch_split<1, false>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
-    else if (!rows) e = launch_split<2, false>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
-    else e = launch_split<2, true>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
+    if (!rows) e = launch_split<false>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
+    else e = launch_split<true>(n_wgs, st, a, hdr, row_info, ws_o, ws_ml, pmax, tq, rk, rw, steps_per_us);
     prof_after(st);
     if (e) return e;
     if ((e = hip_check(hipGetLastError(), "merged split launch"))) return e;
