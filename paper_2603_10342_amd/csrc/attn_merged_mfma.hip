@@ -41,9 +41,6 @@ namespace {
 
 using namespace splitk;
 
-#ifndef AG_MERGED_TILE_US
-#define AG_MERGED_TILE_US 2.15f
-#endif
 
 constexpr int kMinSteps = kMinSplit / 32;       // a streaming share is at least this many steps (256 keys)
 constexpr int kMinTiles = kMinSplit / 64;       // a tile share at least this many tiles (256 keys)
@@ -54,7 +51,7 @@ constexpr int kRowsLds = (tile32::kKStages + 2) * tile32::kTile;        // 80 Ki
 // 32 keys per microsecond on the whole device (6.0 TB/s) however many they are, as long as they are enough to
 // saturate the memory system; a single streaming workgroup cannot take a step in less than 0.57 us (what one CU
 // can draw, for its two workgroups).
-constexpr float kTileUs = AG_MERGED_TILE_US;
+constexpr float kTileUs = 2.15f;
 constexpr float kDeviceStepsPerUs = 369.0f;
 constexpr float kStepUsAlone = 0.57f;
 
