@@ -1,9 +1,10 @@
 #!/usr/bin/env python3
 """Benchmark of the paged-KV attention hot path on one MI355X.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads decode,cold,resume,mixed]
-  further workloads, not in the default run: merged (the decode queue in one launch), controller (the
-  TPOT-driven loop on partitions), cushare (throughput against CU share), copycal (counter yardstick)
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workloads decode,cold,resume,mixed,merged]
+  (merged: the scheduler's decode queue in one launch)
+  further workloads, not in the default run: controller (the TPOT-driven loop on partitions), cushare
+  (throughput against CU share), copycal (counter yardstick)
 
 Prints ONE JSON line.  The headline metric is decode-attention HBM GB/s on the
 decode-only configuration (64 sessions, contexts U[1024, 4096], 32/8 heads,
@@ -849,7 +850,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workloads", default="decode,cold,resume,mixed")
+    ap.add_argument("--workloads", default="decode,cold,resume,mixed,merged")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sets", type=int, default=4, help="disjoint session sets the decode step rotates over")
     ap.add_argument("--mixed-steps", type=int, default=2000)
