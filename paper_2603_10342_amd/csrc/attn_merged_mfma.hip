@@ -41,7 +41,6 @@ namespace {
 
 using namespace splitk;
 
-
 constexpr int kMinSteps = kMinSplit / 32;       // a streaming share is at least this many steps (256 keys)
 constexpr int kMinTiles = kMinSplit / 64;       // a tile share at least this many tiles (256 keys)
 constexpr int kSmemBytes = 4 * 16 * D * 4 + 2 * 4 * 16 * 4;             // 33280: partials of four waves
@@ -57,7 +56,8 @@ constexpr float kStepUsAlone = 0.57f;
 
 __device__ __forceinline__ int steps_of(int ctx) { return ctx > 0 ? (ctx + 31) >> 5 : 0; }
 __device__ __forceinline__ int tiles_of(int ctx) { return ctx > 0 ? (ctx + 63) >> 6 : 0; }
-// Segments a pair of n units may be cut into when shares are at least `least` units.
+// Segments a pair may be cut into: a pair has at most ceil(max_ctx / 32) steps (half as many tiles), and a share is
+// at least kMinSteps steps (kMinTiles tiles).
 inline int pieces_max(int max_ctx) { return (((max_ctx + 31) / 32) - 1) / kMinSteps + 2; }
 
 // How a session's N rows are cut.  rk: rows of a full keys item; rw: rows of a full rows item, 0 if the launch
