@@ -211,10 +211,12 @@ AG_API ag_status ag_decode_step(const ag_kv_cache* cache, const void* k_new, con
  * Algorithm 1: a request joins Q_D if it is a decode or no longer than B_prefill).  Semantics are exactly
  * ag_attn_resume's: session s brings new_lens[s] >= 0 query rows at positions prefix_lens[s] + i that attend
  * causally to the session's keys; a decode is the case new_lens[s] = 1, prefix_lens[s] = ctx - 1.  What
- * differs is the schedule: the keys of each session are split over workgroups as in ag_attn_decode, which
- * pays when sessions bring few rows (the launch is then bound by reading K and V); when the longest chunk
- * (max_new) has about a hundred rows or more the call runs ag_attn_resume's kernel instead, which is faster
- * from there on.  Arguments as ag_attn_resume, plus a device workspace of at least
+ * differs is the schedule: the keys of the batch are dealt to the workgroups in equal shares as in
+ * ag_attn_decode (streaming work for decodes and chunks of a few rows, tile work for longer chunks, side by
+ * side), which pays when sessions bring few rows (the launch is then bound by reading K and V); when the
+ * longest chunk (max_new) has 144 rows or more the call runs ag_attn_resume's kernel instead, which is faster
+ * from about there on.  The launch is sized for the CUs `stream` may use (its CU mask, if it has one).
+ * Arguments as ag_attn_resume, plus a device workspace of at least
  * ag_attn_merged_workspace_bytes(total_new, num_q_heads, max_ctx) bytes, 16-byte aligned, which the call may
  * overwrite entirely (AG_ERR_WORKSPACE if smaller).  Calls sharing a workspace must be ordered on one stream.
  */
