@@ -38,6 +38,10 @@ MIXES = {
     # contexts that end exactly on page / step / part boundaries
     "boundaries": ([15, 16, 31, 127, 128, 255, 511, 1024, 2047, 4095], [1, 1, 1, 1, 1, 1, 1, 1, 1, 1]),
     "only_resumes": ([2000, 1000], [48, 64]),
+    # a chunk long enough for the call to hand the launch to the prefill kernel (same semantics), next to decodes
+    "handed_to_the_prefill_kernel": ([500, 1200, 77], [1, 150, 1]),
+    # ... and the longest chunk the merged kernel keeps (four full rows items and a remainder)
+    "longest_kept": ([500, 1200, 77], [1, 143, 1]),
 }
 
 
